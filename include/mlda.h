@@ -1,0 +1,150 @@
+/*
+ * mlda — collapsed Gibbs sampling for LDA on one AMD MI355X (gfx950).
+ *
+ * C ABI of libmlda.so.  The problem statement follows the paper's Section 2.1:
+ * a corpus of D documents over a vocabulary of V words, K topics and the
+ * hyper-parameters alpha and beta go in; the topic assignment of every token,
+ * the document-topic counts theta, the topic-word counts phi and a
+ * log-likelihood come out, one sampling pass ("iteration") at a time.
+ *
+ * What one iteration computes (Sections 2.1 and 6):
+ *   every token (document d, word v, current topic o) draws a new topic from
+ *       p(k) ~ (theta_dk + alpha)(phi_kv + beta) / (n_k + beta V)          (Eq. 1)
+ *   evaluated as p = p1 + p2 with p1 = theta_dk p*(k), p2 = alpha p*(k),
+ *   p*(k) = (phi_kv + beta)/(n_k + beta V), S = sum p1, Q = sum p2       (Eq. 6-8),
+ *   one uniform choosing the bucket and the smallest k whose prefix sum
+ *   exceeds the draw (Section 6.1.1, Algorithm 2);
+ *   then phi and theta are rebuilt from the new assignments (Section 6.2).
+ * Fixed by this library where the paper leaves a choice:
+ *   - all tokens of an iteration see the counts as they stood when the
+ *     iteration began, each with the token's own assignment removed;
+ *   - p*(k) is the fp64 quotient rounded once to fp32, products and sums are fp64;
+ *   - the uniform of token t in iteration i is the top 53 bits of the first two
+ *     words of Philox4x32-10 with counter (t lo, t hi, i, 0) and key
+ *     (seed lo, seed hi), where t is the token's index in the caller's
+ *     document-major word_ids array; x = u (S+Q); x < S takes the p1 bucket
+ *     (topics ascending) at position x, otherwise the p2 bucket at x - S;
+ *   - iteration 0 of the same generator gives the initial topics, floor(u K).
+ *
+ * Conventions
+ *   - Every function returns MLDA_OK (0) or a negative code; mlda_last_error()
+ *     gives the message of the calling thread's most recent failure.
+ *   - "host" pointers are ordinary CPU memory owned by the caller and only read
+ *     or written during the call.  The device workspace and the HIP stream are
+ *     the caller's too (e.g. a torch uint8 CUDA tensor and
+ *     torch.cuda.current_stream().cuda_stream); the library allocates no device
+ *     memory, keeps the workspace until mlda_destroy, and launches all work on
+ *     that stream.  Getters synchronise the stream.
+ *   - A context is not thread-safe.  Token order at the boundary is always the
+ *     caller's document-major order; the word-major order used on the device is
+ *     internal.
+ */
+#ifndef MLDA_H
+#define MLDA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MLDA_OK        0
+#define MLDA_EINVAL   -1   /* bad argument (null pointer, K outside [1,65535], alpha or beta <= 0,
+                              word id outside [0,V), doc_ptr not starting at 0 or decreasing,
+                              2^31 or more tokens, topic >= K) */
+#define MLDA_ENOMEM   -2   /* device workspace smaller than mlda_workspace_bytes, or host malloc failed */
+#define MLDA_EHIP     -3   /* a HIP call failed; the message names it */
+#define MLDA_ENOTSUP  -4   /* K too large for this device's LDS (the word's p* column must fit) */
+
+#define MLDA_STEP_LOGLIK 1u /* mlda_step flag: also evaluate the log-likelihood after each iteration */
+
+typedef struct mlda_ctx mlda_ctx;   /* opaque */
+
+/* Bytes of device workspace mlda_create needs for a corpus of D documents and T
+ * tokens (an upper bound that depends on the sizes only).  bytes: host, out. */
+int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* bytes);
+
+/*
+ * Build a context (Section 2.1: the corpus; Section 6.1.2: tokens are put in
+ * word-first order; Section 6.2: a document->token map is built on the CPU).
+ *   doc_ptr   host, D+1 entries, doc_ptr[0] = 0, non-decreasing; document d owns
+ *             tokens doc_ptr[d] .. doc_ptr[d+1]-1.  T = doc_ptr[D] < 2^31.
+ *   word_ids  host, T entries, each in [0,V).
+ *   dev_workspace  DEVICE pointer, 256-byte aligned, workspace_bytes long.
+ *   hip_stream     a hipStream_t (0 = the default stream).
+ * The corpus is copied; the host arrays may be released after the call.  No
+ * topics are assigned yet: call mlda_init_random or mlda_set_assignments next.
+ */
+int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
+                int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Random initial topics (Section 2.1), z[t] = floor(u(seed, 0, t) K); rebuilds all
+ * counts; the iteration counter becomes 0. */
+int mlda_init_random(mlda_ctx* ctx);
+
+/* Install assignments (host, T entries, document-major, each < K), rebuild all counts,
+ * and set the number of iterations already done (the next pass uses iter+1 in the
+ * generator's counter): resumes a run from a saved state. */
+int mlda_set_assignments(mlda_ctx* ctx, const uint16_t* z, int32_t iter);
+
+/* Run n_iters iterations: sample every token (Section 6.1), rebuild phi and n_k, then
+ * theta (Section 6.2); with MLDA_STEP_LOGLIK also the log-likelihood of each new state.
+ * Asynchronous on the context's stream. */
+int mlda_step(mlda_ctx* ctx, int32_t n_iters, uint32_t flags);
+
+/* Number of iterations done so far. iter: host, out. */
+int mlda_iteration(const mlda_ctx* ctx, int32_t* iter);
+
+/* Current assignments, document-major.  z: host, T entries, out. */
+int mlda_get_assignments(mlda_ctx* ctx, uint16_t* z);
+
+/* phi as a word-major matrix: n_wk[v*K + k] = tokens of word v with topic k.
+ * n_wk: host, V*K entries, out. */
+int mlda_get_word_topic(mlda_ctx* ctx, int32_t* n_wk);
+
+/* n_k[k] = sum_v phi_kv, the denominator term of Eq. 1.  n_k: host, K entries, out. */
+int mlda_get_topic_totals(mlda_ctx* ctx, int32_t* n_k);
+
+/* Number of non-zero entries of theta. nnz: host, out. */
+int mlda_get_doc_topic_nnz(mlda_ctx* ctx, int64_t* nnz);
+
+/* theta in CSR form (Sections 3.1 and 6.1.3: 16-bit column indices): row_ptr host D+1
+ * entries; topics / counts host, mlda_get_doc_topic_nnz entries each; within a row the
+ * topics ascend and every count is positive. */
+int mlda_get_doc_topic_csr(mlda_ctx* ctx, int64_t* row_ptr, uint16_t* topics, int32_t* counts);
+
+/* Joint collapsed log-likelihood log p(w, z | alpha, beta) of the current state
+ * (the "log-likelihood per token" of Section 7.2 is this value divided by T).
+ * ll: host, out. */
+int mlda_get_loglik(mlda_ctx* ctx, double* ll);
+
+/*
+ * Kernel times of the iterations of the most recent mlda_step, from HIP events on
+ * the context's stream.  ms: host, capacity_iters rows of 4 doubles (sampling, rebuild
+ * phi and n_k, rebuild theta, log-likelihood), out; n_iters: host, out, rows filled
+ * (the last min(n, capacity_iters, 1024) iterations of that step).
+ */
+int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* n_iters);
+
+/* Algorithmic bytes the sampling kernel must move for the current state (Section 3.1's
+ * accounting with p* shared per word tile): 16 T + 6 sum_d N_d nnz_d + 4 K #tiles.
+ * bytes: host, out. */
+int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes);
+
+/* Releases the context (host memory and events); the workspace stays the caller's. */
+void mlda_destroy(mlda_ctx* ctx);
+
+/* n uniforms of iteration iter for tokens token0 .. token0+n-1 into DEVICE memory
+ * (out_dev: device, n doubles), on hip_stream: exposes the generator for checking. */
+int mlda_philox_uniform(uint64_t seed, uint32_t iter, uint64_t token0, int64_t n,
+                        double* out_dev, void* hip_stream);
+
+const char* mlda_strerror(int code);
+const char* mlda_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLDA_H */

@@ -1,0 +1,201 @@
+// Model update kernels (paper Section 6.2): phi and n_k from the word-sorted
+// assignments, theta rows from the document->token map; plus the order changes at
+// the boundary and the log-likelihood reductions.
+#pragma once
+#include "device_util.hpp"
+#include "kernels_sample.hpp"
+
+namespace mlda {
+
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Rows of words whose tokens span several tiles are accumulated with atomics and must
+// start at zero.  grid = (#split words, ceil(K / blockDim)).
+__global__ void zero_rows_kernel(const int32_t* words, int32_t* n_wk, int32_t K) {
+    const int k = (int)(blockIdx.y * blockDim.x + threadIdx.x);
+    if (k < K) n_wk[(size_t)words[blockIdx.x] * (size_t)K + k] = 0;
+}
+
+// Update phi (Section 6.2: word by word, atomics with good locality): a workgroup
+// histograms one tile's assignments in LDS, then stores the word's row outright if the
+// tile is the whole word, else adds its non-zero bins to the row.
+__global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* tiles, const uint16_t* z,
+                                                       int32_t* n_wk, int32_t K) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    int32_t* hist = reinterpret_cast<int32_t*>(lds);
+    const Tile tl = tiles[blockIdx.x];
+    const int tid = (int)threadIdx.x;
+    for (int k = tid; k < K; k += 256) hist[k] = 0;
+    __syncthreads();
+    for (int i = tid; i < tl.count; i += 256) atomicAdd(&hist[z[tl.begin + i]], 1);
+    __syncthreads();
+    int32_t* row = n_wk + (size_t)tl.word * (size_t)K;
+    if (tl.whole) {
+        for (int k = tid; k < K; k += 256) row[k] = hist[k];
+    } else {
+        for (int k = tid; k < K; k += 256) {
+            const int c = hist[k];
+            if (c != 0) atomicAdd(&row[k], c);
+        }
+    }
+}
+
+// n_k[k] = number of tokens with topic k.  Persistent workgroups, each over a contiguous
+// share of the tokens; n_k must be zero on entry.
+__global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, int64_t T,
+                                                           int32_t* n_k, int32_t K) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    int32_t* hist = reinterpret_cast<int32_t*>(lds);
+    const int tid = (int)threadIdx.x;
+    for (int k = tid; k < K; k += 256) hist[k] = 0;
+    __syncthreads();
+    const int64_t per = (T + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x, hi = (lo + per < T) ? lo + per : T;
+    for (int64_t t = lo + tid; t < hi; t += 256) atomicAdd(&hist[z[t]], 1);
+    __syncthreads();
+    for (int k = tid; k < K; k += 256) {
+        const int c = hist[k];
+        if (c != 0) atomicAdd(&n_k[k], c);
+    }
+}
+
+// Update theta (Section 6.2): document by document, (1) a dense K-long histogram of the
+// document's assignments, reached through the document->token map, (2) compaction of the
+// non-zero bins into the row (topics ascending).  One wave per document, persistent; the
+// dense row lives in LDS and is left all-zero for the next document.  Row layout:
+// int32 counts[round4(nnz)] then uint16 topics[round4(nnz)], padding entries zero.
+__global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_ptr,
+                                                           const int32_t* doc_map,
+                                                           const uint16_t* z, uint2* row_rec,
+                                                           unsigned char* slots, int64_t D,
+                                                           int32_t K) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    int32_t* hist = reinterpret_cast<int32_t*>(lds);
+    const int lane = (int)threadIdx.x;
+    for (int k = lane; k < K; k += kWave) hist[k] = 0;
+    __syncthreads();
+    for (int64_t d = blockIdx.x; d < D; d += gridDim.x) {
+        const int b = doc_ptr[d], n = doc_ptr[d + 1] - b;
+        int fresh = 0;
+        for (int i = lane; i < n; i += kWave) {
+            const int k = (int)z[doc_map[b + i]];
+            fresh += (atomicAdd(&hist[k], 1) == 0) ? 1 : 0;     // first token of a topic
+        }
+        const int nnz = wave_sum(fresh);
+        __syncthreads();
+        const int nnz_pad = (nnz + 3) & ~3;
+        const uint32_t off = row_rec[d].x;
+        int32_t* cnt = reinterpret_cast<int32_t*>(slots + (size_t)off * 16u);
+        uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
+        int filled = 0;
+        for (int base = 0; base < K; base += kWave) {
+            const int k = base + lane;
+            const int c = (k < K) ? hist[k] : 0;
+            const uint64_t m = __ballot(c > 0);
+            if (m == 0) continue;
+            if (c > 0) {
+                const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
+                cnt[at] = c;
+                top[at] = (uint16_t)k;
+                hist[k] = 0;
+            }
+            filled += __popcll((unsigned long long)m);
+        }
+        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = 0; }
+        if (lane == 0) row_rec[d].y = (uint32_t)nnz;
+        __syncthreads();
+    }
+}
+
+// Boundary order changes.  doc_map[t] = word-major position of document-major token t;
+// tok_id[pos] = document-major index of word-major position pos.
+__global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,
+                                    uint16_t* z_doc, int64_t T) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) z_doc[t] = z_word[doc_map[t]];
+}
+
+__global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_id,
+                                     uint16_t* z_word, int64_t T) {
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos < T) z_word[pos] = z_doc[tok_id[pos]];
+}
+
+// ------------------------------------------------------------------ log-likelihood
+// log p(w,z) = sum_k [lgG(V beta) - lgG(n_k + V beta)] + sum_{v,k} [lgG(n_wk + beta) - lgG(beta)]
+//            + sum_d [lgG(K alpha) - lgG(N_d + K alpha)] + sum_{d,k} [lgG(n_dk + alpha) - lgG(alpha)]
+// Each workgroup writes one fp64 partial; a last single-workgroup kernel adds them in a
+// fixed order, so the value does not depend on scheduling.
+
+__device__ __forceinline__ void block_partial_store(double v, double* partial) {
+    __shared__ double wsum[16];
+    const int lane = lane_id(), wave = (int)threadIdx.x / kWave;
+    const double s = wave_sum(v);
+    if (lane == 0) wsum[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        for (int w = 0; w < (int)blockDim.x / kWave; ++w) tot += wsum[w];
+        partial[blockIdx.x] = tot;
+    }
+}
+
+__global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_wk, int64_t n_cells,
+                                                               const int32_t* n_k, int32_t K,
+                                                               double beta, double v_beta,
+                                                               double* partial) {
+    const double lg_beta = lgamma(beta);
+    double acc = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_cells; i += stride) {
+        const int c = n_wk[i];
+        if (c > 0) acc += lgamma((double)c + beta) - lg_beta;
+    }
+    if (blockIdx.x == 0) {
+        const double lg_vb = lgamma(v_beta);
+        for (int k = (int)threadIdx.x; k < K; k += (int)blockDim.x)
+            acc += lg_vb - lgamma((double)n_k[k] + v_beta);
+    }
+    block_partial_store(acc, partial);
+}
+
+// One wave per document at a time (4 waves per workgroup, persistent).
+__global__ __launch_bounds__(256) void loglik_doc_side_kernel(const int32_t* doc_ptr,
+                                                              const uint2* row_rec,
+                                                              const unsigned char* slots,
+                                                              int64_t D, double alpha,
+                                                              double k_alpha, double* partial) {
+    const double lg_alpha = lgamma(alpha), lg_ka = lgamma(k_alpha);
+    const int lane = lane_id();
+    const int64_t wave_global = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    double acc = 0.0;
+    for (int64_t d = wave_global; d < D; d += n_waves) {
+        const uint2 rec = row_rec[d];
+        const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)rec.x * 16u);
+        for (int j = lane; j < (int)rec.y; j += kWave)
+            acc += lgamma((double)cnt[j] + alpha) - lg_alpha;
+        if (lane == 0)
+            acc += lg_ka - lgamma((double)(doc_ptr[d + 1] - doc_ptr[d]) + k_alpha);
+    }
+    block_partial_store(acc, partial);
+}
+
+__global__ __launch_bounds__(256) void loglik_final_kernel(const double* partial, int n,
+                                                           double* out) {
+    __shared__ double buf[256];
+    double acc = 0.0;
+    for (int i = (int)threadIdx.x; i < n; i += 256) acc += partial[i];
+    buf[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) buf[threadIdx.x] += buf[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = buf[0];
+}
+
+}  // namespace mlda

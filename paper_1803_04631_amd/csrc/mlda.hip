@@ -1,0 +1,653 @@
+// libmlda.so: C ABI, context and host-side preprocessing (see include/mlda.h).
+//
+// Paper sections behind the host steps: Section 6.1.2 (tokens are sorted word-first and
+// the tokens of heavy words are split over several workgroups that are issued first),
+// Section 6.2 (a document->token map built on the CPU lets the theta update find a
+// document's tokens in the word-sorted arrays), Algorithm 1 WorkSchedule1 with one
+// chunk on one GPU (transfer once, then iterate on the device).
+#include "../../include/mlda.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "kernels_rebuild.hpp"
+#include "kernels_sample.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string& msg) {
+    g_last_error = msg;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                  \
+    do {                                                                               \
+        hipError_t e_ = (expr);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return fail(MLDA_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr size_t kAlign = 256;        // workspace sub-buffer alignment
+constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
+constexpr int kSampleWaves = 4;
+constexpr int kMaxTimedIters = 1024;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
+
+size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
+    return align_up((size_t)(((cap + 3) & ~(int64_t)3) * 6), kSlotAlign);
+}
+
+// Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
+struct Layout {
+    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, row_rec, slots, n_wk, n_k, tiles, split,
+        ll_partial, ll_value, total;
+    void finish() {
+        size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &row_rec, &slots,
+                           &n_wk, &n_k, &tiles, &split, &ll_partial, &ll_value};
+        total = 0;
+        for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
+    }
+};
+
+constexpr int kLoglikBlocks = 2048;
+
+Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
+                  size_t n_split) {
+    Layout L{};
+    L.tok_doc = (size_t)T * 4;
+    L.tok_id = (size_t)T * 4;
+    L.doc_map = (size_t)T * 4;
+    L.z0 = (size_t)T * 2;
+    L.z1 = (size_t)T * 2;
+    L.doc_ptr = (size_t)(D + 1) * 4;
+    L.row_rec = (size_t)D * 8;
+    L.slots = slots_bytes;
+    L.n_wk = (size_t)V * (size_t)K * 4;
+    L.n_k = (size_t)K * 4;
+    L.tiles = n_tiles * sizeof(mlda::Tile);
+    L.split = n_split * 4;
+    L.ll_partial = (size_t)2 * kLoglikBlocks * 8;
+    L.ll_value = 8;
+    L.finish();
+    return L;
+}
+
+Layout layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
+    const size_t tile = (size_t)tile_tokens_for(K);
+    const size_t slots = (size_t)T * 6 + (size_t)D * (18 + kSlotAlign);
+    const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
+    return layout_for(D, T, V, K, slots, n_tiles, (size_t)V);
+}
+
+template <class F>
+void parallel_chunks(int n_chunks, F&& body) {
+    std::vector<std::thread> pool;
+    for (int c = 1; c < n_chunks; ++c) pool.emplace_back([&, c] { body(c); });
+    body(0);
+    for (auto& t : pool) t.join();
+}
+
+}  // namespace
+
+struct mlda_ctx {
+    int64_t D = 0, T = 0;
+    int32_t V = 0, K = 0, Kpad = 0;
+    double alpha = 0, beta = 0;
+    uint64_t seed = 0;
+    int32_t iter = 0;
+    hipStream_t stream = nullptr;
+    int n_cus = 0, lds_limit = 0;
+
+    int32_t *tok_doc = nullptr, *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    int32_t *n_wk = nullptr, *n_k = nullptr, *split_words = nullptr;
+    uint16_t* z[2] = {nullptr, nullptr};
+    int cur = 0;
+    uint2* row_rec = nullptr;
+    unsigned char* slots = nullptr;
+    size_t slots_bytes = 0;
+    mlda::Tile* tiles = nullptr;
+    int32_t n_tiles = 0, n_split = 0;
+    double *ll_partial = nullptr, *ll_value = nullptr;
+
+    std::vector<int64_t> doc_ptr_host;
+    bool has_state = false, ll_fresh = false;
+
+    std::vector<hipEvent_t> events;     // 5 per timed iteration
+    int32_t timed_iters = 0;            // iterations of the last step that carry events
+    size_t sample_lds = 0;
+};
+
+namespace {
+
+int launch_check(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(MLDA_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    return MLDA_OK;
+}
+
+int blocks_for(int64_t n, int per) { return (int)((n + per - 1) / per); }
+
+// phi, n_k and theta from the assignments in z (word-major).  ev: optional events
+// [after phi+n_k, after theta].
+int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_t* ev_theta) {
+    using namespace mlda;
+    const size_t hist_bytes = (size_t)c->K * 4;
+    if (c->n_split > 0) {
+        dim3 grid((unsigned)c->n_split, (unsigned)blocks_for(c->K, 256));
+        hipLaunchKernelGGL(zero_rows_kernel, grid, dim3(256), 0, c->stream, c->split_words, c->n_wk,
+                           c->K);
+    }
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream, c->n_k,
+                       (int64_t)c->K, 0);
+    if (c->n_tiles > 0) {
+        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_tiles), dim3(256), hist_bytes,
+                           c->stream, c->tiles, z, c->n_wk, c->K);
+        const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
+        hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes,
+                           c->stream, z, c->T, c->n_k, c->K);
+    }
+    if (ev_phi) HIP_TRY(hipEventRecord(*ev_phi, c->stream));
+    if (c->D > 0) {
+        const int per_cu = std::max(1, std::min(16, (int)(c->lds_limit / std::max<size_t>(hist_bytes, 1))));
+        const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * per_cu);
+        hipLaunchKernelGGL(theta_rows_kernel, dim3((unsigned)grid), dim3(kWave), hist_bytes, c->stream,
+                           c->doc_ptr, c->doc_map, z, c->row_rec, c->slots, c->D, c->K);
+    }
+    if (ev_theta) HIP_TRY(hipEventRecord(*ev_theta, c->stream));
+    return launch_check("rebuild kernels");
+}
+
+int launch_loglik(mlda_ctx* c) {
+    using namespace mlda;
+    const int64_t cells = (int64_t)c->V * c->K;
+    hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->n_wk,
+                       cells, c->n_k, c->K, c->beta, (double)c->V * c->beta, c->ll_partial);
+    hipLaunchKernelGGL(loglik_doc_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
+                       c->doc_ptr, c->row_rec, c->slots, c->D, c->alpha, (double)c->K * c->alpha,
+                       c->ll_partial + kLoglikBlocks);
+    hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial,
+                       2 * kLoglikBlocks, c->ll_value);
+    c->ll_fresh = true;
+    return launch_check("log-likelihood kernels");
+}
+
+int need_state(const mlda_ctx* c) {
+    if (!c) return fail(MLDA_EINVAL, "null context");
+    if (!c->has_state)
+        return fail(MLDA_EINVAL, "no topic assignments yet: call mlda_init_random or mlda_set_assignments");
+    return MLDA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mlda_strerror(int code) {
+    switch (code) {
+        case MLDA_OK: return "ok";
+        case MLDA_EINVAL: return "invalid argument";
+        case MLDA_ENOMEM: return "workspace too small or out of host memory";
+        case MLDA_EHIP: return "HIP call failed";
+        case MLDA_ENOTSUP: return "K too large for the device's LDS";
+        default: return "unknown error";
+    }
+}
+
+const char* mlda_last_error(void) { return g_last_error.c_str(); }
+
+int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* bytes) {
+    if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
+    if (D < 0 || T < 0 || V < 1 || K < 1 || K > 65535 || T >= ((int64_t)1 << 31))
+        return fail(MLDA_EINVAL, "need D >= 0, 0 <= T < 2^31, V >= 1, 1 <= K <= 65535");
+    *bytes = layout_bound(D, T, V, K).total;
+    return MLDA_OK;
+}
+
+int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
+                int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(MLDA_EINVAL, "out is null");
+    *out = nullptr;
+    if (!doc_ptr) return fail(MLDA_EINVAL, "doc_ptr is null");
+    if (D < 0 || V < 1) return fail(MLDA_EINVAL, "need D >= 0 and V >= 1");
+    if (K < 1 || K > 65535) return fail(MLDA_EINVAL, "K must be in [1, 65535] (16-bit topic indices)");
+    if (!(alpha > 0.0) || !(beta > 0.0) || !std::isfinite(alpha) || !std::isfinite(beta))
+        return fail(MLDA_EINVAL, "alpha and beta must be positive and finite");
+    if (doc_ptr[0] != 0) return fail(MLDA_EINVAL, "doc_ptr[0] must be 0");
+    for (int64_t d = 0; d < D; ++d)
+        if (doc_ptr[d + 1] < doc_ptr[d]) return fail(MLDA_EINVAL, "doc_ptr must be non-decreasing");
+    const int64_t T = doc_ptr[D];
+    if (T >= ((int64_t)1 << 31)) return fail(MLDA_EINVAL, "2^31 or more tokens");
+    if (T > 0 && !word_ids) return fail(MLDA_EINVAL, "word_ids is null");
+    if (!dev_workspace) return fail(MLDA_EINVAL, "dev_workspace is null");
+    if (((uintptr_t)dev_workspace) % kAlign != 0)
+        return fail(MLDA_EINVAL, "dev_workspace must be 256-byte aligned");
+    size_t need_bound = 0;
+    if (mlda_workspace_bytes(D, T, V, K, &need_bound) != MLDA_OK) return MLDA_EINVAL;
+    if (workspace_bytes < need_bound)
+        return fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
+                                     std::to_string(need_bound));
+    {
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, dev_workspace);
+        if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
+            (void)hipGetLastError();
+            return fail(MLDA_EINVAL, "dev_workspace is not device memory");
+        }
+    }
+
+    int dev = 0, n_cus = 0, lds_limit = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    const int32_t Kpad = (K + mlda::kGroup - 1) / mlda::kGroup * mlda::kGroup;
+    const size_t sample_lds = (size_t)Kpad * 4 + (size_t)(Kpad / mlda::kGroup) * 8;
+    if (sample_lds > (size_t)lds_limit)
+        return fail(MLDA_ENOTSUP, "K = " + std::to_string(K) + " needs " + std::to_string(sample_lds) +
+                                      " bytes of LDS per workgroup, the device allows " +
+                                      std::to_string(lds_limit));
+
+    // ---- word-first order (stable counting sort over chunks of the token range)
+    const int n_chunks = (int)std::max<int64_t>(
+        1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 32, T / 65536 + 1}));
+    std::vector<std::vector<int32_t>> chunk_hist(n_chunks);
+    std::vector<int> chunk_bad(n_chunks, 0);
+    auto chunk_lo = [&](int c) { return T / n_chunks * c + std::min<int64_t>(c, T % n_chunks); };
+    try {
+        parallel_chunks(n_chunks, [&](int c) {
+            auto& h = chunk_hist[c];
+            h.assign((size_t)V, 0);
+            for (int64_t t = chunk_lo(c); t < chunk_lo(c + 1); ++t) {
+                const int32_t w = word_ids[t];
+                if (w < 0 || w >= V) { chunk_bad[c] = 1; return; }
+                ++h[w];
+            }
+        });
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    for (int c = 0; c < n_chunks; ++c)
+        if (chunk_bad[c]) return fail(MLDA_EINVAL, "word id outside [0, V)");
+
+    std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_doc, tok_id, doc_map, doc_ptr32, split_words;
+    std::vector<uint2> row_rec;
+    std::vector<mlda::Tile> tiles;
+    size_t slots_bytes = 0;
+    try {
+        for (int32_t v = 0; v < V; ++v) {
+            int32_t n = 0;
+            for (int c = 0; c < n_chunks; ++c) {
+                const int32_t h = chunk_hist[c][v];
+                chunk_hist[c][v] = n;          // becomes the chunk's offset inside the word
+                n += h;
+            }
+            word_ptr[v + 1] = word_ptr[v] + n;
+        }
+        tok_doc.resize((size_t)T);
+        tok_id.resize((size_t)T);
+        doc_map.resize((size_t)T);
+        parallel_chunks(n_chunks, [&](int c) {
+            auto& start = chunk_hist[c];
+            const int64_t lo = chunk_lo(c), hi = chunk_lo(c + 1);
+            int64_t d = std::upper_bound(doc_ptr, doc_ptr + D + 1, lo) - doc_ptr - 1;
+            for (int64_t t = lo; t < hi; ++t) {
+                while (doc_ptr[d + 1] <= t) ++d;
+                const int32_t w = word_ids[t];
+                const int32_t pos = word_ptr[w] + start[w]++;
+                tok_id[pos] = (int32_t)t;
+                tok_doc[pos] = (int32_t)d;
+                doc_map[t] = pos;
+            }
+        });
+        chunk_hist.clear();
+
+        // ---- theta row slots: fixed capacity min(N_d, K), so rows never move
+        doc_ptr32.resize((size_t)D + 1);
+        row_rec.resize((size_t)D);
+        for (int64_t d = 0; d <= D; ++d) doc_ptr32[d] = (int32_t)doc_ptr[d];
+        for (int64_t d = 0; d < D; ++d) {
+            const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
+            row_rec[d] = make_uint2((uint32_t)(slots_bytes / 16), 0u);
+            slots_bytes += slot_bytes_for(cap);
+        }
+
+        // ---- tiles of one word each, largest first (Section 6.1.2)
+        const int32_t tile = tile_tokens_for(K);
+        for (int32_t v = 0; v < V; ++v) {
+            const int32_t n = word_ptr[v + 1] - word_ptr[v];
+            if (n > tile) split_words.push_back(v);
+            for (int32_t b = 0; b < n; b += tile)
+                tiles.push_back(mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), n <= tile ? 1 : 0});
+        }
+        std::stable_sort(tiles.begin(), tiles.end(),
+                         [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+
+    const Layout L = layout_for(D, T, V, K, slots_bytes, tiles.size(), split_words.size());
+    if (L.total > workspace_bytes)
+        return fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
+                                     std::to_string(L.total));
+
+    mlda_ctx* c = new (std::nothrow) mlda_ctx();
+    if (!c) return fail(MLDA_ENOMEM, "out of host memory");
+    c->D = D; c->T = T; c->V = V; c->K = K; c->Kpad = Kpad;
+    c->alpha = alpha; c->beta = beta; c->seed = seed;
+    c->stream = (hipStream_t)hip_stream;
+    c->n_cus = n_cus; c->lds_limit = lds_limit; c->sample_lds = sample_lds;
+    c->n_tiles = (int32_t)tiles.size();
+    c->n_split = (int32_t)split_words.size();
+    c->slots_bytes = slots_bytes;
+    c->doc_ptr_host.assign(doc_ptr, doc_ptr + D + 1);
+
+    unsigned char* p = (unsigned char*)dev_workspace;
+    auto take = [&](size_t bytes) { unsigned char* q = p; p += bytes; return q; };
+    c->tok_doc = (int32_t*)take(L.tok_doc);
+    c->tok_id = (int32_t*)take(L.tok_id);
+    c->doc_map = (int32_t*)take(L.doc_map);
+    c->z[0] = (uint16_t*)take(L.z0);
+    c->z[1] = (uint16_t*)take(L.z1);
+    c->doc_ptr = (int32_t*)take(L.doc_ptr);
+    c->row_rec = (uint2*)take(L.row_rec);
+    c->slots = take(L.slots);
+    c->n_wk = (int32_t*)take(L.n_wk);
+    c->n_k = (int32_t*)take(L.n_k);
+    c->tiles = (mlda::Tile*)take(L.tiles);
+    c->split_words = (int32_t*)take(L.split);
+    c->ll_partial = (double*)take(L.ll_partial);
+    c->ll_value = (double*)take(L.ll_value);
+
+    auto up = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+        if (bytes == 0) return hipSuccess;
+        return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->stream);
+    };
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = up(c->tok_doc, tok_doc.data(), (size_t)T * 4);
+    if (e == hipSuccess) e = up(c->tok_id, tok_id.data(), (size_t)T * 4);
+    if (e == hipSuccess) e = up(c->doc_map, doc_map.data(), (size_t)T * 4);
+    if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
+    if (e == hipSuccess) e = up(c->row_rec, row_rec.data(), (size_t)D * 8);
+    if (e == hipSuccess) e = up(c->tiles, tiles.data(), tiles.size() * sizeof(mlda::Tile));
+    if (e == hipSuccess) e = up(c->split_words, split_words.data(), split_words.size() * 4);
+    if (e == hipSuccess) {
+        // rows of words without tokens are never written again: start phi at zero
+        const int64_t cells = (int64_t)V * K;
+        hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
+                           c->n_wk, cells, 0);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess && sample_lds > 48 * 1024)
+        e = hipFuncSetAttribute((const void*)mlda::sample_kernel<kSampleWaves>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sample_lds);
+    if (e == hipSuccess && (size_t)K * 4 > 48 * 1024) {
+        e = hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)mlda::theta_rows_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
+    }
+    *out = c;
+    return MLDA_OK;
+}
+
+int mlda_init_random(mlda_ctx* c) {
+    if (!c) return fail(MLDA_EINVAL, "null context");
+    if (c->T > 0)
+        hipLaunchKernelGGL(mlda::init_topics_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                           c->stream, c->tok_id, c->z[c->cur], c->T, c->K, c->seed);
+    int rc = launch_check("init_topics_kernel");
+    if (rc != MLDA_OK) return rc;
+    rc = rebuild_counts(c, c->z[c->cur], nullptr, nullptr);
+    if (rc != MLDA_OK) return rc;
+    c->iter = 0;
+    c->has_state = true;
+    c->ll_fresh = false;
+    return MLDA_OK;
+}
+
+int mlda_set_assignments(mlda_ctx* c, const uint16_t* z, int32_t iter) {
+    if (!c) return fail(MLDA_EINVAL, "null context");
+    if (c->T > 0 && !z) return fail(MLDA_EINVAL, "z is null");
+    if (iter < 0) return fail(MLDA_EINVAL, "iter must be >= 0");
+    for (int64_t t = 0; t < c->T; ++t)
+        if (z[t] >= c->K) return fail(MLDA_EINVAL, "topic >= K in z");
+    if (c->T > 0) {
+        uint16_t* tmp = c->z[c->cur ^ 1];
+        HIP_TRY(hipMemcpyAsync(tmp, z, (size_t)c->T * 2, hipMemcpyHostToDevice, c->stream));
+        hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                           c->stream, tmp, c->tok_id, c->z[c->cur], c->T);
+        HIP_TRY(hipStreamSynchronize(c->stream));     // the caller's z may go away after return
+    }
+    int rc = rebuild_counts(c, c->z[c->cur], nullptr, nullptr);
+    if (rc != MLDA_OK) return rc;
+    c->iter = iter;
+    c->has_state = true;
+    c->ll_fresh = false;
+    return MLDA_OK;
+}
+
+int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (n_iters < 0) return fail(MLDA_EINVAL, "n_iters must be >= 0");
+    const int32_t timed = std::min(n_iters, kMaxTimedIters);
+    while ((int32_t)c->events.size() < timed * 5) {
+        hipEvent_t ev;
+        HIP_TRY(hipEventCreate(&ev));
+        c->events.push_back(ev);
+    }
+    c->timed_iters = timed;
+    for (int32_t i = 0; i < n_iters; ++i) {
+        const int32_t slot = i - (n_iters - timed);
+        hipEvent_t* ev = slot >= 0 ? &c->events[(size_t)slot * 5] : nullptr;
+        if (ev) HIP_TRY(hipEventRecord(ev[0], c->stream));
+        uint16_t* z_next = c->z[c->cur ^ 1];
+        if (c->n_tiles > 0) {
+            mlda::SampleArgs a;
+            a.tiles = c->tiles;
+            a.tok_doc = c->tok_doc;
+            a.tok_id = c->tok_id;
+            a.z_cur = c->z[c->cur];
+            a.z_next = z_next;
+            a.row_rec = c->row_rec;
+            a.slots = c->slots;
+            a.n_wk = c->n_wk;
+            a.n_k = c->n_k;
+            a.K = c->K;
+            a.Kpad = c->Kpad;
+            a.alpha = c->alpha;
+            a.beta = c->beta;
+            a.beta_V = c->beta * (double)c->V;
+            a.seed = c->seed;
+            a.iter = (uint32_t)(c->iter + 1);
+            hipLaunchKernelGGL(mlda::sample_kernel<kSampleWaves>, dim3((unsigned)c->n_tiles),
+                               dim3(kSampleWaves * mlda::kWave), c->sample_lds, c->stream, a);
+            rc = launch_check("sample_kernel");
+            if (rc != MLDA_OK) return rc;
+        }
+        if (ev) HIP_TRY(hipEventRecord(ev[1], c->stream));
+        rc = rebuild_counts(c, z_next, ev ? &ev[2] : nullptr, ev ? &ev[3] : nullptr);
+        if (rc != MLDA_OK) return rc;
+        c->cur ^= 1;
+        c->iter += 1;
+        c->ll_fresh = false;
+        if (flags & MLDA_STEP_LOGLIK) {
+            rc = launch_loglik(c);
+            if (rc != MLDA_OK) return rc;
+        }
+        if (ev) HIP_TRY(hipEventRecord(ev[4], c->stream));
+    }
+    return MLDA_OK;
+}
+
+int mlda_iteration(const mlda_ctx* c, int32_t* iter) {
+    if (!c || !iter) return fail(MLDA_EINVAL, "null argument");
+    *iter = c->iter;
+    return MLDA_OK;
+}
+
+int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (c->T == 0) return MLDA_OK;
+    if (!z) return fail(MLDA_EINVAL, "z is null");
+    uint16_t* tmp = c->z[c->cur ^ 1];      // free between steps
+    hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
+                       c->z[c->cur], c->doc_map, tmp, c->T);
+    HIP_TRY(hipMemcpyAsync(z, tmp, (size_t)c->T * 2, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+int mlda_get_word_topic(mlda_ctx* c, int32_t* n_wk) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!n_wk) return fail(MLDA_EINVAL, "n_wk is null");
+    HIP_TRY(hipMemcpyAsync(n_wk, c->n_wk, (size_t)c->V * c->K * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+int mlda_get_topic_totals(mlda_ctx* c, int32_t* n_k) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!n_k) return fail(MLDA_EINVAL, "n_k is null");
+    HIP_TRY(hipMemcpyAsync(n_k, c->n_k, (size_t)c->K * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+static int fetch_row_rec(mlda_ctx* c, std::vector<uint2>& rec) {
+    try { rec.resize((size_t)c->D); } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    if (c->D > 0)
+        HIP_TRY(hipMemcpyAsync(rec.data(), c->row_rec, (size_t)c->D * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+int mlda_get_doc_topic_nnz(mlda_ctx* c, int64_t* nnz) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!nnz) return fail(MLDA_EINVAL, "nnz is null");
+    std::vector<uint2> rec;
+    rc = fetch_row_rec(c, rec);
+    if (rc != MLDA_OK) return rc;
+    int64_t n = 0;
+    for (const uint2& r : rec) n += r.y;
+    *nnz = n;
+    return MLDA_OK;
+}
+
+int mlda_get_doc_topic_csr(mlda_ctx* c, int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!row_ptr) return fail(MLDA_EINVAL, "row_ptr is null");
+    std::vector<uint2> rec;
+    rc = fetch_row_rec(c, rec);
+    if (rc != MLDA_OK) return rc;
+    std::vector<unsigned char> slots;
+    try { slots.resize(c->slots_bytes); } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    if (c->slots_bytes > 0)
+        HIP_TRY(hipMemcpy(slots.data(), c->slots, c->slots_bytes, hipMemcpyDeviceToHost));
+    row_ptr[0] = 0;
+    for (int64_t d = 0; d < c->D; ++d) row_ptr[d + 1] = row_ptr[d] + rec[d].y;
+    if (row_ptr[c->D] > 0 && (!topics || !counts)) return fail(MLDA_EINVAL, "topics or counts is null");
+    for (int64_t d = 0; d < c->D; ++d) {
+        const uint32_t nnz = rec[d].y, pad = (nnz + 3u) & ~3u;
+        const unsigned char* base = slots.data() + (size_t)rec[d].x * 16;
+        if (nnz == 0) continue;
+        std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
+        std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
+    }
+    return MLDA_OK;
+}
+
+int mlda_get_loglik(mlda_ctx* c, double* ll) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!ll) return fail(MLDA_EINVAL, "ll is null");
+    if (!c->ll_fresh) {
+        rc = launch_loglik(c);
+        if (rc != MLDA_OK) return rc;
+    }
+    HIP_TRY(hipMemcpyAsync(ll, c->ll_value, 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+int mlda_get_timing(mlda_ctx* c, double* ms, int32_t capacity_iters, int32_t* n_iters) {
+    if (!c || !ms || !n_iters || capacity_iters < 0) return fail(MLDA_EINVAL, "bad argument");
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const int32_t n = std::min(c->timed_iters, capacity_iters);
+    const int32_t first = c->timed_iters - n;
+    for (int32_t i = 0; i < n; ++i) {
+        hipEvent_t* ev = &c->events[(size_t)(first + i) * 5];
+        for (int j = 0; j < 4; ++j) {
+            float t = 0.f;
+            HIP_TRY(hipEventElapsedTime(&t, ev[j], ev[j + 1]));
+            ms[(size_t)i * 4 + j] = (double)t;
+        }
+    }
+    *n_iters = n;
+    return MLDA_OK;
+}
+
+int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes) {
+    int rc = need_state(c);
+    if (rc != MLDA_OK) return rc;
+    if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
+    std::vector<uint2> rec;
+    rc = fetch_row_rec(c, rec);
+    if (rc != MLDA_OK) return rc;
+    double row_entries = 0.0;       // sum over tokens of the nnz of the token's theta row
+    for (int64_t d = 0; d < c->D; ++d)
+        row_entries += (double)(c->doc_ptr_host[d + 1] - c->doc_ptr_host[d]) * (double)rec[d].y;
+    // per token: document id 4, token id 4, old topic 2, new topic 2, row record 8
+    *bytes = 20.0 * (double)c->T + 6.0 * row_entries + 4.0 * (double)c->K * (double)c->n_tiles;
+    return MLDA_OK;
+}
+
+void mlda_destroy(mlda_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (hipEvent_t ev : c->events) (void)hipEventDestroy(ev);
+    delete c;
+}
+
+int mlda_philox_uniform(uint64_t seed, uint32_t iter, uint64_t token0, int64_t n, double* out_dev,
+                        void* hip_stream) {
+    if (n < 0) return fail(MLDA_EINVAL, "n must be >= 0");
+    if (n == 0) return MLDA_OK;
+    if (!out_dev) return fail(MLDA_EINVAL, "out_dev is null");
+    hipLaunchKernelGGL(mlda::philox_uniform_kernel, dim3(blocks_for(n, 256)), dim3(256), 0,
+                       (hipStream_t)hip_stream, seed, iter, token0, n, out_dev);
+    return launch_check("philox_uniform_kernel");
+}
+
+}  // extern "C"

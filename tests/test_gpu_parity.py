@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Bars: integer work (initial topics, counts, CSR rows) bit-exact;
+sampled assignments may differ from the oracle on at most 1e-6 of the tokens (fp64
+rounding order at a CDF boundary); log-likelihood within 1e-5 relative."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import corpus_synth
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+Z_MISMATCH_FRACTION = 1e-6
+LL_RTOL = 1e-5
+SEED = corpus_synth.SAMPLER_SEED
+
+
+@pytest.fixture(scope="module")
+def mlda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests need a real MI355X")
+    import paper_1803_04631_amd as m
+    m.load_library()
+    return m
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def check_counts(model, c, z, V, K):
+    """Counts held by the library == a recount of z by the oracle (bit-exact)."""
+    n_wk, n_k = oracle.count_word_topic(c.word_ids, z, V, K)
+    assert np.array_equal(model.word_topic(), n_wk)
+    assert np.array_equal(model.topic_totals(), n_k)
+    row_ptr, topics, counts = oracle.doc_topic_csr(c.doc_ptr, z, K)
+    g_ptr, g_top, g_cnt = model.doc_topic_csr()
+    assert np.array_equal(g_ptr, row_ptr)
+    assert np.array_equal(g_top, topics)
+    assert np.array_equal(g_cnt, counts)
+    assert model.doc_topic_nnz() == row_ptr[-1]
+    assert n_wk.sum() == counts.sum() == len(z) and n_k.sum() == len(z)
+    return n_wk, n_k
+
+
+def check_step(model, c, z, V, K, alpha, beta, seed, it):
+    """One iteration from state z on both sides; returns the GPU's new state."""
+    n_wk, n_k = oracle.count_word_topic(c.word_ids, z, V, K)
+    want = oracle.iteration(c.doc_ptr, c.word_ids, z, V, K, alpha, beta, seed, it, n_wk, n_k)
+    model.step(1)
+    got = model.assignments()
+    assert got.max(initial=0) < K
+    bad = int((got != want).sum())
+    assert bad <= Z_MISMATCH_FRACTION * len(z), f"{bad} of {len(z)} assignments differ at iteration {it}"
+    n_wk2, n_k2 = check_counts(model, c, got, V, K)
+    ll = oracle.loglik(c.doc_ptr, got, V, K, alpha, beta, n_wk2, n_k2)
+    assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
+    return got
+
+
+def test_philox_bitwise(mlda):
+    n = 1 << 20
+    for seed, it, t0 in [(SEED, 1, 0), (2**63 + 12345, 77, 2**32 - 1000), (0, 0, 2**40)]:
+        say("philox", seed, it, t0)
+        got = mlda.philox_uniform(seed, it, t0, n).cpu().numpy()
+        assert np.array_equal(got, oracle.uniforms(seed, it, t0, n))
+
+
+@pytest.mark.parametrize("name,iters", [("C1", 10), ("C2", 6)])
+def test_named_config_free_running(mlda, name, iters):
+    """Configs C1 and C2: initial state, then every iteration, against the oracle."""
+    c = corpus_synth.generate(name)
+    cfg = c.config
+    say(name, "T", c.T)
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    model.init_random()
+    z = oracle.init_topics(c.T, cfg.K, SEED)
+    assert np.array_equal(model.assignments(), z)
+    check_counts(model, c, z, cfg.V, cfg.K)
+    nnz = [model.doc_topic_nnz()]
+    for it in range(1, iters + 1):
+        say(name, "iteration", it)
+        z = check_step(model, c, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, it)
+        nnz.append(model.doc_topic_nnz())
+        assert model.iteration == it
+    assert nnz[-1] < nnz[0]          # Section 7.1: theta gets sparser over the first iterations
+    model.close()
+
+
+def test_converged_like_state(mlda):
+    """Start from the topics the corpus was generated with (sparse theta rows)."""
+    c = corpus_synth.generate("C2")
+    cfg = c.config
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    model.set_assignments(c.z_true, it=40)
+    assert model.iteration == 40
+    assert np.array_equal(model.assignments(), c.z_true)
+    check_counts(model, c, c.z_true, cfg.V, cfg.K)
+    check_step(model, c, c.z_true, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, 41)
+    model.close()
+
+
+EDGE_CASES = [
+    # name,                 D,   V,    K,   mean_len
+    ("single_topic",        50,  30,   1,   10),
+    ("two_topics",          50,  30,   2,   10),
+    ("k_not_mult_of_16",    80,  60,   37,  30),
+    ("k_just_over_wave",    60,  90,   65,  300),     # rows longer than one wave
+    ("long_rows",           40,  500,  300, 2500),    # nnz up to ~300: several row chunks
+    ("one_word_vocab",      40,  1,    8,   20),
+    ("large_k_small_docs",  300, 2000, 10000, 120),   # C5-like K: 45 KB of LDS per tile
+    ("short_docs",          3000, 200, 16,  1.2),     # many single-token documents (S = 0)
+]
+
+
+@pytest.mark.parametrize("case", EDGE_CASES, ids=[c[0] for c in EDGE_CASES])
+def test_edge_shapes(mlda, case):
+    name, D, V, K, mean_len = case
+    c = corpus_synth.tiny(D=D, V=V, K=K, mean_len=mean_len, seed=len(name), name=name)
+    alpha, beta = 50.0 / K, 0.01
+    say(name, "T", c.T)
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, SEED)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, SEED)
+    assert np.array_equal(model.assignments(), z)
+    for it in (1, 2, 3):
+        z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
+    model.close()
+
+
+def test_empty_documents_and_unused_words(mlda):
+    base = corpus_synth.tiny(D=30, V=40, K=12, mean_len=9, seed=2)
+    lens = np.diff(base.doc_ptr)
+    # interleave empty documents, keep the same tokens; shift word ids so that word 0
+    # and the last words never occur
+    new_lens = np.zeros(2 * len(lens) + 3, dtype=np.int64)
+    new_lens[1:2 * len(lens):2] = lens
+    doc_ptr = np.concatenate([[0], np.cumsum(new_lens)]).astype(np.int64)
+    words = (base.word_ids + 1).astype(np.int32)
+    V, K, alpha, beta = 50, 12, 0.7, 0.05
+
+    class C:  # minimal corpus record
+        pass
+    c = C(); c.doc_ptr = doc_ptr; c.word_ids = words; c.T = len(words)
+    model = mlda.Mlda(doc_ptr, words, V, K, alpha, beta, 9)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, 9)
+    for it in (1, 2):
+        z = check_step(model, c, z, V, K, alpha, beta, 9, it)
+    n_wk = model.word_topic()
+    assert n_wk[0].sum() == 0 and n_wk[41:].sum() == 0
+    model.close()
+
+
+def test_empty_corpus(mlda):
+    doc_ptr = np.zeros(4, dtype=np.int64)
+    model = mlda.Mlda(doc_ptr, np.zeros(0, dtype=np.int32), 5, 3, 0.5, 0.01, 1)
+    model.init_random()
+    model.step(2)
+    assert model.iteration == 2 and len(model.assignments()) == 0
+    assert model.word_topic().sum() == 0 and model.doc_topic_nnz() == 0
+    row_ptr, topics, counts = model.doc_topic_csr()
+    assert np.array_equal(row_ptr, np.zeros(4)) and len(topics) == 0
+    # all counts zero: every lgamma difference vanishes
+    assert abs(model.loglik()) < 1e-9
+    model.close()
+
+
+def test_deterministic_and_resumable(mlda):
+    """Two runs are bit-identical; 6 iterations == 3 + export + new context + import + 3."""
+    c = corpus_synth.generate("C1")
+    cfg = c.config
+    args = (c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    a = mlda.Mlda(*args); a.init_random(); a.step(6)
+    b = mlda.Mlda(*args); b.init_random(); b.step(6)
+    za = a.assignments()
+    assert np.array_equal(za, b.assignments())
+    assert a.loglik() == b.loglik()
+    r = mlda.Mlda(*args); r.init_random(); r.step(3)
+    saved, it = r.assignments(), r.iteration
+    r.close()
+    r2 = mlda.Mlda(*args); r2.set_assignments(saved, it=it); r2.step(3)
+    assert np.array_equal(r2.assignments(), za) and r2.iteration == 6
+    assert np.array_equal(r2.word_topic(), a.word_topic())
+    # another seed is another chain
+    d = mlda.Mlda(*args[:-1], SEED + 1); d.init_random(); d.step(1)
+    assert not np.array_equal(d.assignments()[:1000], za[:1000])
+    for m in (a, b, r2, d):
+        m.close()
+
+
+def test_step_with_loglik_flag_and_timing(mlda):
+    c = corpus_synth.generate("C1")
+    cfg = c.config
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    model.init_random()
+    ll0 = model.loglik()
+    model.step(4, loglik=True)
+    ms = model.timing()
+    assert ms.shape == (4, 4) and np.all(ms[:, :3] > 0) and np.all(ms < 1000)
+    z = model.assignments()
+    n_wk, n_k = oracle.count_word_topic(c.word_ids, z, cfg.V, cfg.K)
+    ll = oracle.loglik(c.doc_ptr, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
+    assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
+    assert model.loglik() > ll0
+    # the algorithmic byte count follows its definition
+    lens = np.diff(c.doc_ptr)
+    row_ptr, _, _ = model.doc_topic_csr()
+    n_tiles = int(np.ceil(np.bincount(c.word_ids, minlength=cfg.V) / 1024).sum())
+    want = 20.0 * c.T + 6.0 * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
+    assert model.sampler_bytes() == want
+    model.close()
+
+
+def test_device_side_argument_errors(mlda):
+    import torch
+    lib = mlda.load_library()
+    c = corpus_synth.tiny(D=10, V=20, K=4, mean_len=5, seed=1)
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, 20, 4, 0.5, 0.01, 1)
+    with pytest.raises(mlda.MldaError) as e:           # no state yet
+        model.step(1)
+    assert e.value.code == -1
+    with pytest.raises(mlda.MldaError):
+        model.assignments()
+    with pytest.raises(mlda.MldaError):                # topic >= K
+        model.set_assignments(np.full(c.T, 4, dtype=np.uint16))
+    model.init_random()
+    with pytest.raises(mlda.MldaError):
+        model.step(-1)
+    model.close()
+    bad_words = c.word_ids.copy(); bad_words[3] = 20
+    with pytest.raises(mlda.MldaError) as e:
+        mlda.Mlda(c.doc_ptr, bad_words, 20, 4, 0.5, 0.01, 1)
+    assert e.value.code == -1 and "word id" in str(e.value)
+    # host memory handed in as the device workspace
+    ctx = ctypes.c_void_p()
+    host = np.zeros(1 << 22, dtype=np.uint8)
+    addr = (host.ctypes.data + 255) // 256 * 256
+    rc = lib.mlda_create(ctypes.addressof(ctx), c.doc_ptr.ctypes.data, c.word_ids.ctypes.data,
+                         10, 20, 4, 0.5, 0.01, 1, ctypes.c_void_p(addr), (1 << 22) - 256, None)
+    assert rc == -1 and b"not device memory" in lib.mlda_last_error()
+    # K whose p* column cannot fit in LDS
+    big_k = 60000
+    need = mlda.workspace_bytes(10, c.T, 20, big_k)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    rc = lib.mlda_create(ctypes.addressof(ctx), c.doc_ptr.ctypes.data, c.word_ids.ctypes.data,
+                         10, 20, big_k, 0.5, 0.01, 1, ws.data_ptr(), need, None)
+    assert rc == -4 and b"LDS" in lib.mlda_last_error()
