@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark: sampled tokens/sec per iteration of collapsed Gibbs sampling for LDA on one
+MI355X (the paper's metric, Eq. 2), on a synthetic corpus shaped like the paper's larger
+workload, plus the sampling kernel's HBM roofline fraction and the CPU oracle timed
+beside it.
+
+A "step" is one whole iteration: sampling, rebuild of phi and n_k, rebuild of theta and
+the log-likelihood of the new state.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per sampling launch from rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by a
+# copy kernel of known size); filled in from the summaries under profiles/ per workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, seed, target_tokens):
+    """The oracle's full pass, as it stands, on a bounded sample of the same workload:
+    the first documents of the same configuration as a corpus of their own."""
+    import numpy as np
+    import corpus_synth
+    import oracle
+    scale = min(1.0, target_tokens / (cfg.D * cfg.mean_len))
+    sample = corpus_synth.generate(cfg, scale=scale)
+    z = oracle.init_topics(sample.T, cfg.K, seed)
+    n_wk, n_k = oracle.count_word_topic(sample.word_ids, z, cfg.V, cfg.K)
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    z1 = oracle.iteration(sample.doc_ptr, sample.word_ids, z, cfg.V, cfg.K, cfg.alpha, cfg.beta,
+                          seed, 1, n_wk, n_k, threads=threads)
+    n_wk, n_k = oracle.count_word_topic(sample.word_ids, z1, cfg.V, cfg.K)
+    oracle.doc_topic_csr(sample.doc_ptr, z1, cfg.K)
+    oracle.loglik(sample.doc_ptr, z1, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
+    dt = time.perf_counter() - t0
+    return {
+        "value": sample.T / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": "one oracle iteration (resample + recount + log-likelihood) from the random "
+                  "initial state on the first %d documents (%d tokens) of the same configuration; "
+                  "sampling uses %d OpenMP threads, the recounts one" % (len(sample.doc_ptr) - 1,
+                                                                         sample.T, threads),
+        "seconds": dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C4", help="C1..C5 (default C4, the largest single-GPU workload)")
+    ap.add_argument("--state", default="init", choices=["init", "generated"],
+                    help="start from random topics (as the paper does) or from the topics the corpus "
+                         "was generated with (a converged-like, sparse theta)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=float, default=0.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (--gpus 1); the multi-GPU phi "
+                 "reduction of the paper's Section 5.2 is not part of it")
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: launched with WORLD_SIZE > 1, but this build runs on ONE GPU only")
+
+    import numpy as np
+    import torch
+    import corpus_synth
+    import paper_1803_04631_amd as mlda
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cfg = corpus_synth.CONFIGS[args.config]
+    seed = corpus_synth.SAMPLER_SEED
+
+    t0 = time.perf_counter()
+    corpus = corpus_synth.generate(cfg)
+    log("corpus %s: D=%d V=%d K=%d T=%d generated in %.1f s" % (cfg.name, cfg.D, cfg.V, cfg.K, corpus.T,
+                                                               time.perf_counter() - t0))
+    t0 = time.perf_counter()
+    model = mlda.Mlda(corpus.doc_ptr, corpus.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed,
+                      device="cuda:0")
+    if args.state == "init":
+        model.init_random()
+    else:
+        model.set_assignments(corpus.z_true, it=0)
+    model.synchronize()
+    T = corpus.T
+    log("resident on the GPU in %.1f s (workspace %.2f GB)" % (time.perf_counter() - t0,
+                                                              model.workspace.numel() / 1e9))
+    corpus.word_ids = corpus.z_true = None
+
+    if args.warmup > 0:
+        model.step(args.warmup, loglik=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model.step(args.steps, loglik=True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms = model.timing()                       # [steps, 4] HIP-event times on the library's stream
+    algo_bytes = model.sampler_bytes()        # [steps] algorithmic bytes of each sampling launch
+    ll = model.loglik()
+    nnz = model.doc_topic_nnz()
+    mean_ms = ms.mean(axis=0)
+    sample_ms = float(mean_ms[0])
+    achieved = float((algo_bytes / (ms[:, 0] * 1e-3)).mean()) / 1e9      # GB/s, per launch then mean
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, args.state))
+    value = T * args.steps / elapsed
+    log("per iteration: sample %.2f ms, phi %.2f ms, theta %.2f ms, loglik %.2f ms; wall %.2f ms"
+        % (*mean_ms, elapsed / args.steps * 1e3))
+    log("tokens/s %.4g; sampler %.1f GB/s algorithmic (%.1f%% of %.0f); LL/token %.4f; theta nnz/doc %.1f"
+        % (value, achieved, 100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS, ll / T, nnz / cfg.D))
+
+    out = {
+        "metric": "sampled tokens/sec per iteration (1 GPU)",
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: D=%d V=%d K=%d T=%d, alpha=50/K, beta=0.01, %s start, iterations %d..%d"
+                        % (cfg.name, cfg.D, cfg.V, cfg.K, T,
+                           "random-topic" if args.state == "init" else "generated-topic",
+                           args.warmup + 1, args.warmup + args.steps),
+            "step": "sample + rebuild phi/n_k + rebuild theta + log-likelihood",
+            "ms_sample": sample_ms, "ms_rebuild_phi": float(mean_ms[1]),
+            "ms_rebuild_theta": float(mean_ms[2]), "ms_loglik": float(mean_ms[3]),
+            "tokens_per_s_without_loglik": T / (float(mean_ms[:3].sum()) * 1e-3),
+            "loglik_per_token": ll / T,
+            "theta_nnz_per_doc": nnz / cfg.D,
+            "sampler_bytes_per_token": float(algo_bytes.mean()) / T,
+        },
+        "roofline": {
+            "kernel": "sample_kernel",
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "avg_launch_ms": sample_ms,
+            "algorithmic_bytes_per_launch": float(algo_bytes.mean()),
+        },
+    }
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        target = args.cpu_sample_tokens or 1.2e10 / cfg.K      # about 10-30 s of oracle work
+        out["cpu_baseline"] = cpu_baseline(cfg, seed, target)
+        log("oracle: %.4g tokens/s on %d threads (%.1f s)" % (out["cpu_baseline"]["value"],
+                                                              out["cpu_baseline"]["cores"],
+                                                              out["cpu_baseline"]["seconds"]))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

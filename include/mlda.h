@@ -128,10 +128,14 @@ int mlda_get_loglik(mlda_ctx* ctx, double* ll);
  */
 int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* n_iters);
 
-/* Algorithmic bytes the sampling kernel must move for the current state (Section 3.1's
- * accounting with p* shared per word tile): 16 T + 6 sum_d N_d nnz_d + 4 K #tiles.
- * bytes: host, out. */
-int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes);
+/*
+ * Algorithmic bytes each sampling launch of the most recent mlda_step had to move
+ * (Section 3.1's accounting, with p* shared per word tile): per token 20 bytes (document
+ * id, token id, old and new topic, row record) plus 6 bytes per entry of its theta row,
+ * plus 4 K bytes of phi per tile.  bytes: host, capacity_iters doubles, out; rows as in
+ * mlda_get_timing.
+ */
+int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);
 
 /* Releases the context (host memory and events); the workspace stays the caller's. */
 void mlda_destroy(mlda_ctx* ctx);

@@ -51,7 +51,7 @@ def load_library() -> ctypes.CDLL:
         "mlda_get_doc_topic_csr": [p, p, p, p],
         "mlda_get_loglik": [p, p],
         "mlda_get_timing": [p, p, i32, p],
-        "mlda_get_sampler_bytes": [p, p],
+        "mlda_get_sampler_bytes": [p, p, i32, p],
         "mlda_philox_uniform": [u64, u32, u64, i64, p, p],
     }
     for name, argtypes in sig.items():
@@ -186,10 +186,13 @@ class Mlda:
         _check(self._lib.mlda_get_timing(self._ctx, ms.ctypes.data, capacity, ctypes.addressof(n)))
         return ms[:n.value]
 
-    def sampler_bytes(self) -> float:
-        b = ctypes.c_double()
-        _check(self._lib.mlda_get_sampler_bytes(self._ctx, ctypes.addressof(b)))
-        return b.value
+    def sampler_bytes(self, capacity: int = 1024) -> np.ndarray:
+        """Algorithmic bytes of each sampling launch of the last step (same rows as timing)."""
+        b = np.zeros(capacity, dtype=np.float64)
+        n = ctypes.c_int32()
+        _check(self._lib.mlda_get_sampler_bytes(self._ctx, b.ctypes.data, capacity,
+                                                ctypes.addressof(n)))
+        return b[:n.value]
 
     def close(self):
         if getattr(self, "_ctx", None):

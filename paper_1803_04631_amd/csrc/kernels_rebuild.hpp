@@ -7,6 +7,8 @@
 
 namespace mlda {
 
+__global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
+
 __global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -71,12 +73,14 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_pt
                                                            const int32_t* doc_map,
                                                            const uint16_t* z, uint2* row_rec,
                                                            unsigned char* slots, int64_t D,
-                                                           int32_t K) {
+                                                           int32_t K,
+                                                           unsigned long long* row_entries) {
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* hist = reinterpret_cast<int32_t*>(lds);
     const int lane = (int)threadIdx.x;
     for (int k = lane; k < K; k += kWave) hist[k] = 0;
     __syncthreads();
+    unsigned long long visited = 0;      // sum of N_d * nnz_d over this wave's documents
     for (int64_t d = blockIdx.x; d < D; d += gridDim.x) {
         const int b = doc_ptr[d], n = doc_ptr[d + 1] - b;
         int fresh = 0;
@@ -106,8 +110,11 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_pt
         }
         if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = 0; }
         if (lane == 0) row_rec[d].y = (uint32_t)nnz;
+        visited += (unsigned long long)n * (unsigned long long)nnz;
         __syncthreads();
     }
+    // row entries the next sampling pass will read: one row walk per token
+    if (lane == 0 && visited != 0) atomicAdd(row_entries, visited);
 }
 
 // Boundary order changes.  doc_map[t] = word-major position of document-major token t;

@@ -53,16 +53,17 @@ size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
 // Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
 struct Layout {
     size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, row_rec, slots, n_wk, n_k, tiles, split,
-        ll_partial, ll_value, total;
+        ll_partial, ll_value, row_entries, total;
     void finish() {
         size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &row_rec, &slots,
-                           &n_wk, &n_k, &tiles, &split, &ll_partial, &ll_value};
+                           &n_wk, &n_k, &tiles, &split, &ll_partial, &ll_value, &row_entries};
         total = 0;
         for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
     }
 };
 
 constexpr int kLoglikBlocks = 2048;
+constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entries (> kMaxTimedIters)
 
 Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
                   size_t n_split) {
@@ -81,6 +82,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
     L.split = n_split * 4;
     L.ll_partial = (size_t)2 * kLoglikBlocks * 8;
     L.ll_value = 8;
+    L.row_entries = (size_t)kEntryRing * 8;
     L.finish();
     return L;
 }
@@ -121,6 +123,9 @@ struct mlda_ctx {
     mlda::Tile* tiles = nullptr;
     int32_t n_tiles = 0, n_split = 0;
     double *ll_partial = nullptr, *ll_value = nullptr;
+    unsigned long long* row_entries = nullptr;   // ring: [r % kEntryRing] written by rebuild r
+    int64_t rebuilds = 0;                        // rebuilds launched so far
+    int32_t last_step_iters = 0;
 
     std::vector<int64_t> doc_ptr_host;
     bool has_state = false, ll_fresh = false;
@@ -163,9 +168,12 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
     if (c->D > 0) {
         const int per_cu = std::max(1, std::min(16, (int)(c->lds_limit / std::max<size_t>(hist_bytes, 1))));
         const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * per_cu);
+        unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
+        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
         hipLaunchKernelGGL(theta_rows_kernel, dim3((unsigned)grid), dim3(kWave), hist_bytes, c->stream,
-                           c->doc_ptr, c->doc_map, z, c->row_rec, c->slots, c->D, c->K);
+                           c->doc_ptr, c->doc_map, z, c->row_rec, c->slots, c->D, c->K, entries);
     }
+    c->rebuilds += 1;
     if (ev_theta) HIP_TRY(hipEventRecord(*ev_theta, c->stream));
     return launch_check("rebuild kernels");
 }
@@ -370,6 +378,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->split_words = (int32_t*)take(L.split);
     c->ll_partial = (double*)take(L.ll_partial);
     c->ll_value = (double*)take(L.ll_value);
+    c->row_entries = (unsigned long long*)take(L.row_entries);
 
     auto up = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
         if (bytes == 0) return hipSuccess;
@@ -459,6 +468,7 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
         c->events.push_back(ev);
     }
     c->timed_iters = timed;
+    c->last_step_iters = n_iters;
     for (int32_t i = 0; i < n_iters; ++i) {
         const int32_t slot = i - (n_iters - timed);
         hipEvent_t* ev = slot >= 0 ? &c->events[(size_t)slot * 5] : nullptr;
@@ -618,18 +628,25 @@ int mlda_get_timing(mlda_ctx* c, double* ms, int32_t capacity_iters, int32_t* n_
     return MLDA_OK;
 }
 
-int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes) {
+int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, int32_t* n_iters) {
     int rc = need_state(c);
     if (rc != MLDA_OK) return rc;
-    if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
-    std::vector<uint2> rec;
-    rc = fetch_row_rec(c, rec);
-    if (rc != MLDA_OK) return rc;
-    double row_entries = 0.0;       // sum over tokens of the nnz of the token's theta row
-    for (int64_t d = 0; d < c->D; ++d)
-        row_entries += (double)(c->doc_ptr_host[d + 1] - c->doc_ptr_host[d]) * (double)rec[d].y;
-    // per token: document id 4, token id 4, old topic 2, new topic 2, row record 8
-    *bytes = 20.0 * (double)c->T + 6.0 * row_entries + 4.0 * (double)c->K * (double)c->n_tiles;
+    if (!bytes || !n_iters || capacity_iters < 0) return fail(MLDA_EINVAL, "bad argument");
+    const int32_t n = std::min({c->last_step_iters, capacity_iters, kMaxTimedIters});
+    // iteration j of the step (0-based, of last_step_iters) sampled from the state left by
+    // rebuild number (rebuilds - last_step_iters + j - 1)
+    std::vector<unsigned long long> ring((size_t)kEntryRing);
+    HIP_TRY(hipMemcpyAsync(ring.data(), c->row_entries, (size_t)kEntryRing * 8, hipMemcpyDeviceToHost,
+                           c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t j = c->last_step_iters - n + i;
+        const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
+        const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
+        // per token: document id 4, token id 4, old topic 2, new topic 2, row record 8
+        bytes[i] = 20.0 * (double)c->T + 6.0 * row_entries + 4.0 * (double)c->K * (double)c->n_tiles;
+    }
+    *n_iters = n;
     return MLDA_OK;
 }
 

@@ -206,12 +206,20 @@ def test_step_with_loglik_flag_and_timing(mlda):
     ll = oracle.loglik(c.doc_ptr, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
     assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
     assert model.loglik() > ll0
-    # the algorithmic byte count follows its definition
-    lens = np.diff(c.doc_ptr)
-    row_ptr, _, _ = model.doc_topic_csr()
+    # the algorithmic byte count of each launch follows its definition: the state a launch
+    # samples from is the one before it
     n_tiles = int(np.ceil(np.bincount(c.word_ids, minlength=cfg.V) / 1024).sum())
-    want = 20.0 * c.T + 6.0 * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
-    assert model.sampler_bytes() == want
+    lens = np.diff(c.doc_ptr)
+    before = oracle.doc_topic_csr(c.doc_ptr, model.assignments(), cfg.K)[0]
+    model.step(2)
+    mid = oracle.doc_topic_csr(c.doc_ptr,
+                               oracle.iteration(c.doc_ptr, c.word_ids, z, cfg.V, cfg.K, cfg.alpha,
+                                                cfg.beta, SEED, 5), cfg.K)[0]
+    got = model.sampler_bytes()
+    for row_ptr, b in zip((before, mid), got):
+        want = 20.0 * c.T + 6.0 * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
+        assert b == want
+    assert len(got) == 2
     model.close()
 
 
