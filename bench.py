@@ -70,6 +70,10 @@ def main():
                          "was generated with (a converged-like, sparse theta)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=float, default=0.0)
+    ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
+                    help="also run a plain device copy of this many GiB three times, so that a "
+                         "rocprofv3 --pmc run holds a kernel of known HBM traffic to scale "
+                         "FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (--gpus 1); the multi-GPU phi "
@@ -104,6 +108,15 @@ def main():
                                                               model.workspace.numel() / 1e9))
     corpus.word_ids = corpus.z_true = None
 
+    if args.copy_calibration_gib > 0:
+        n = int(args.copy_calibration_gib * 2**30)
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy calibration: 3 device copies of %d bytes (reads %d, writes %d each)" % (n, n, n))
+        del src, dst
     if args.warmup > 0:
         model.step(args.warmup, loglik=True)
     torch.cuda.synchronize()
@@ -168,7 +181,7 @@ def main():
     del model
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        target = args.cpu_sample_tokens or 1.2e10 / cfg.K      # about 10-30 s of oracle work
+        target = args.cpu_sample_tokens or 1.0e11 / cfg.K      # about 10-30 s of oracle work
         out["cpu_baseline"] = cpu_baseline(cfg, seed, target)
         log("oracle: %.4g tokens/s on %d threads (%.1f s)" % (out["cpu_baseline"]["value"],
                                                               out["cpu_baseline"]["cores"],

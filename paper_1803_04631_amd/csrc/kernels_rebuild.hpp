@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, in
 // document's assignments, reached through the document->token map, (2) compaction of the
 // non-zero bins into the row (topics ascending).  One wave per document, persistent; the
 // dense row lives in LDS and is left all-zero for the next document.  Row layout:
-// int32 counts[round4(nnz)] then uint16 topics[round4(nnz)], padding entries zero.
+// int32 counts[round4(nnz)] then uint16 topics[round4(nnz)]; padding entries hold count 0
+// and topic K.
 __global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_ptr,
                                                            const int32_t* doc_map,
                                                            const uint16_t* z, uint2* row_rec,
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_pt
             }
             filled += __popcll((unsigned long long)m);
         }
-        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = 0; }
+        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
         if (lane == 0) row_rec[d].y = (uint32_t)nnz;
         visited += (unsigned long long)n * (unsigned long long)nnz;
         __syncthreads();

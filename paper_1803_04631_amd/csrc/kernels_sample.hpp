@@ -1,17 +1,23 @@
 // Sampling kernel: one pass of the sparsity-aware sampler (paper Section 6.1, Eq. 6-8,
 // Algorithm 2) over word-sorted tokens.
 //
-// Mapping to gfx950 (the paper's own mapping, warp = sampler with 32-way index trees,
-// was made for 32-wide warps):
-//   - a workgroup owns one tile = up to kTileTokens consecutive tokens of ONE word and
-//     stages that word's p*(k) (Eq. 8) once in LDS as fp32, with fp64 prefix sums over
-//     groups of 16 topics (Section 6.1.2: samplers of a block share the word's data);
-//   - each wave takes 64 tokens at a time.  Everything that is per token and needs no
-//     cooperation is done one token per LANE: the Philox uniform, the token's own-count
-//     correction of p*(o), and the search in the dense bucket p2;
-//   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is
-//     done one token per WAVE with coalesced loads of the row and an fp64 wave scan; the
-//     "smallest k whose prefix exceeds the draw" search (Section 6.1.1) is a ballot.
+// Mapping to gfx950 (the paper's own mapping, one 32-wide warp per sampler with 32-way
+// index trees, was made for NVIDIA warps; measured here, a whole 64-lane wave per token is
+// bound by VALU issue, not by HBM):
+//   - a workgroup owns one tile = up to 1024 (4096 for large K) consecutive tokens of ONE
+//     word and stages that word's p*(k) (Eq. 8) once in LDS as fp32, with fp64 prefix sums
+//     over groups of 16 topics (Section 6.1.2: samplers of a block share the word's data);
+//   - each wave takes 64 tokens at a time.  What is per token and needs no cooperation is
+//     done one token per LANE: the Philox uniform, the token's own-count correction of
+//     p*(o), and the search in the dense bucket p2 (binary search over the group prefixes,
+//     then at most 16 steps);
+//   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
+//     by 16 lanes per token (one DPP row), four tokens per wave at a time: every lane owns
+//     a contiguous run of entries, loaded four at a time as one 16-byte and one 8-byte
+//     load, accumulates them in fp64, and a 4-step in-row DPP scan gives the prefix over
+//     lanes.  The lane whose range holds the draw finds "the smallest k whose prefix exceeds
+//     it" (Section 6.1.1) among its own entries.  Token parameters and results travel
+//     between the per-lane and per-row phases through small per-wave LDS records.
 #pragma once
 #include "device_util.hpp"
 
@@ -31,16 +37,35 @@ struct SampleArgs {
     const uint16_t* z_cur;      // [T] word-major, frozen for the pass
     uint16_t* z_next;           // [T] word-major, written
     const uint2* row_rec;       // [D] {slot offset in 16-byte units, nnz of the theta row}
-    const unsigned char* slots; // theta rows: int32 counts[round4(nnz)] then uint16 topics[round4(nnz)]
+    // theta rows: int32 counts[round4(nnz)] then uint16 topics[round4(nnz)]; padding entries
+    // hold count 0 and topic K
+    const unsigned char* slots;
     const int32_t* n_wk;        // [V][K]
     const int32_t* n_k;         // [K]
-    int32_t K, Kpad;            // Kpad = K rounded up to 16
+    int32_t K, Kpad;            // Kpad = K+1 rounded up to 16: p*(K..Kpad-1) = 0
     double alpha, beta, beta_V;
     uint64_t seed;
     uint32_t iter;
 };
 
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
+constexpr int kRowLanes = 16;   // lanes that walk one token's theta row (one DPP row)
+constexpr int kRowsPerWave = kWave / kRowLanes;
+
+struct __align__(16) TokenRec { // per-lane phase -> per-row phase, 32 bytes
+    uint32_t off;               // slot offset of the token's theta row, 16-byte units
+    int32_t nnz;
+    int32_t o;                  // current topic
+    float w_o;                  // p*(o) with the token itself removed
+    double u;
+    double Qp;                  // alpha * sum_k p*'(k)
+};
+
+// LDS bytes of sample_kernel<kWaves> for a given Kpad.
+__host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
+    return (size_t)Kpad * 4 + (size_t)((Kpad / kGroup + 1) & ~1) * 8 +
+           (size_t)waves * kWave * (8 + sizeof(TokenRec) + 4);
+}
 
 // Dense bucket (p2 = alpha p*', Eq. 6): smallest k with alpha * prefix'(k) > y, where
 // prefix' is the prefix sum of p* with the entry of the token's own topic o replaced by
@@ -67,15 +92,67 @@ __device__ __forceinline__ int dense_bucket_search(const float* pstar, const dou
     return found;
 }
 
+// Move within each row of 16 lanes; lanes without a source read 0.
+template <int kCtrl>
+__device__ __forceinline__ double row_move0(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Inclusive prefix sum inside each row of 16 lanes.  Every lane must be active.
+__device__ __forceinline__ double row_inclusive_sum(double v) {
+    v += row_move0<0x111>(v);   // row_shr:1
+    v += row_move0<0x112>(v);   // row_shr:2
+    v += row_move0<0x114>(v);   // row_shr:4
+    v += row_move0<0x118>(v);   // row_shr:8
+    return v;
+}
+
+// Four entries of a theta row owned by one lane: p1 = (count - [k = o]) * p*'(k), Eq. 6,
+// accumulated onto `base`.  s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
+struct Quad {
+    int k[4];
+    double s[4];
+};
+
+__device__ __forceinline__ Quad row_quad(const int32_t* cnt, const uint16_t* top, int e, bool on,
+                                         int K, int o, float w_o, const float* pstar, double base) {
+    int4 c = make_int4(0, 0, 0, 0);
+    uint2 t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
+    if (on) {
+        c = *reinterpret_cast<const int4*>(cnt + e);
+        t = *reinterpret_cast<const uint2*>(top + e);
+    }
+    Quad q;
+    q.k[0] = (int)(t.x & 0xffffu); q.k[1] = (int)(t.x >> 16);
+    q.k[2] = (int)(t.y & 0xffffu); q.k[3] = (int)(t.y >> 16);
+    const int cc[4] = {c.x, c.y, c.z, c.w};
+    double acc = base;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool own = q.k[j] == o;
+        const float w = own ? w_o : pstar[q.k[j]];
+        acc = fma((double)(cc[j] - (own ? 1 : 0)), (double)w, acc);
+        q.s[j] = acc;
+    }
+    return q;
+}
+
 template <int kWaves>
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
-    float* pstar = reinterpret_cast<float*>(lds);
     const int K = a.K, Kpad = a.Kpad, ng = Kpad / kGroup;
-    double* cp = reinterpret_cast<double*>(lds + (size_t)Kpad * sizeof(float));
+    float* pstar = reinterpret_cast<float*>(lds);
+    double* cp = reinterpret_cast<double*>(lds + (size_t)Kpad * 4);
+    const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    unsigned char* wave_base = lds + (size_t)Kpad * 4 + (size_t)((ng + 1) & ~1) * 8;
+    double* my_y = reinterpret_cast<double*>(wave_base) + wave * kWave;
+    TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base + (size_t)kWaves * kWave * 8) + wave * kWave;
+    int* my_res = reinterpret_cast<int*>(wave_base + (size_t)kWaves * kWave * (8 + sizeof(TokenRec))) +
+                  wave * kWave;
 
     const Tile tl = a.tiles[blockIdx.x];
-    const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int32_t* phi_v = a.n_wk + (size_t)tl.word * (size_t)K;
 
     // ---- stage p*(k) = (phi_kv + beta)/(n_k + beta V) as fp32 (Eq. 8)
@@ -105,109 +182,120 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     __syncthreads();
     const double W = cp[ng - 1];           // sum_k p*(k);  Q = alpha W (Eq. 7)
 
+    const int sl = lane & (kRowLanes - 1), row = lane / kRowLanes;
     const int n_batches = (tl.count + kWave - 1) / kWave;
     for (int b = wave; b < n_batches; b += kWaves) {
         // ---- one token per lane: token, uniform, own-count correction
         const int idx = b * kWave + lane;
         const bool valid = idx < tl.count;
         const int pos = tl.begin + idx;
-        int o = 0, nnz = 0, off = 0;
-        float w_o = 0.f;
-        double u = 0.0, Qp = 0.0, delta = 0.0;
+        TokenRec mine;
+        mine.off = 0; mine.nnz = 0; mine.o = 0; mine.w_o = 0.f; mine.u = 0.0; mine.Qp = 0.0;
+        double delta = 0.0;
         if (valid) {
             const int d = a.tok_doc[pos];
-            o = (int)a.z_cur[pos];
+            mine.o = (int)a.z_cur[pos];
             const uint64_t id = (uint64_t)(uint32_t)a.tok_id[pos];
             const uint2 rec = a.row_rec[d];
-            off = (int)rec.x;
-            nnz = (int)rec.y;
-            u = token_uniform(a.seed, a.iter, id);
+            mine.off = rec.x;
+            mine.nnz = (int)rec.y;
+            mine.u = token_uniform(a.seed, a.iter, id);
             // the token itself is taken out of phi and n_k at its own topic
-            w_o = (float)(((double)(phi_v[o] - 1) + a.beta) / ((double)(a.n_k[o] - 1) + a.beta_V));
-            delta = (double)w_o - (double)pstar[o];
-            Qp = a.alpha * (W + delta);
+            mine.w_o = (float)(((double)(phi_v[mine.o] - 1) + a.beta) /
+                               ((double)(a.n_k[mine.o] - 1) + a.beta_V));
+            delta = (double)mine.w_o - (double)pstar[mine.o];
+            mine.Qp = a.alpha * (W + delta);
         }
-        double S_mine = 0.0;
-        int z_new = -1;                    // -1: the draw falls into the dense bucket
+        my_rec[lane] = mine;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- one token per wave: sparse row of theta, S, and the p1 bucket
+        // ---- one token per row of 16 lanes, four tokens per pass
         const int n_here = min(kWave, tl.count - b * kWave);
-        for (int i = 0; i < n_here; ++i) {
-            const int nnz_i = read_lane(nnz, i);
-            const int o_i = read_lane(o, i);
-            const float w_o_i = read_lane(w_o, i);
-            const double u_i = read_lane(u, i);
-            const double Qp_i = read_lane(Qp, i);
-            const int32_t* cnt = reinterpret_cast<const int32_t*>(
-                a.slots + (size_t)(uint32_t)read_lane(off, i) * 16u);
-            const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz_i + 3) & ~3));
-            double S;
-            int z_sparse = -1;
-            if (nnz_i <= kWave) {
-                const bool have = lane < nnz_i;
-                int c = 0, k = 0;
-                if (have) { c = cnt[lane]; k = (int)top[lane]; }
-                float w = pstar[k];
-                if (have && k == o_i) { c -= 1; w = w_o_i; }
-                const double p1 = (double)c * (double)w;            // Eq. 6, exact product
-                const double incl = wave_inclusive_sum(p1);
-                S = read_lane(incl, kWave - 1);
-                const double x = u_i * (S + Qp_i);
-                if (x < S) {
-                    uint64_t m = __ballot(incl > x);
-                    int j;
-                    if (m != 0) j = __ffsll((unsigned long long)m) - 1;
-                    else j = 63 - __clzll((unsigned long long)__ballot(p1 > 0.0));
-                    z_sparse = read_lane(k, j);
-                }
+        for (int p = 0; p * kRowsPerWave < n_here; ++p) {
+            const int ti = p * kRowsPerWave + row;
+            const bool row_on = ti < n_here;
+            const TokenRec r = my_rec[row_on ? ti : 0];
+            const int nnz = row_on ? r.nnz : 0;
+            const int n4 = (nnz + 4 * kRowLanes - 1) / (4 * kRowLanes);   // quads per lane
+            const int n4max = max(max(read_lane(n4, 0), read_lane(n4, 16)),
+                                  max(read_lane(n4, 32), read_lane(n4, 48)));
+            const int32_t* cnt = reinterpret_cast<const int32_t*>(a.slots + (size_t)r.off * 16u);
+            const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz + 3) & ~3));
+            const int e0 = sl * 4 * n4;                 // this lane owns entries e0 .. e0+4*n4-1
+
+            Quad q;
+            double mine_sum;
+            if (n4max <= 1) {
+                q = row_quad(cnt, top, e0, e0 < nnz, K, r.o, r.w_o, pstar, 0.0);
+                mine_sum = q.s[3];
             } else {
                 double acc = 0.0;
-                for (int base = 0; base < nnz_i; base += kWave) {
-                    const int j = base + lane;
-                    const bool have = j < nnz_i;
-                    int c = 0, k = 0;
-                    if (have) { c = cnt[j]; k = (int)top[j]; }
-                    float w = pstar[k];
-                    if (have && k == o_i) { c -= 1; w = w_o_i; }
-                    acc += (double)c * (double)w;
+                for (int c = 0; c < n4max; ++c) {
+                    const int e = e0 + 4 * c;
+                    q = row_quad(cnt, top, e, c < n4 && e < nnz, K, r.o, r.w_o, pstar, acc);
+                    acc = q.s[3];
                 }
-                S = wave_sum(acc);
-                const double x = u_i * (S + Qp_i);
-                if (x < S) {
-                    double carry = 0.0;
+                mine_sum = acc;
+            }
+            const double incl = row_inclusive_sum(mine_sum);
+            const double excl = row_move0<0x111>(incl);                    // lanes before this one
+            const double S = __shfl(incl, lane | (kRowLanes - 1), kWave);  // Eq. 7, row total
+            const double x = r.u * (S + r.Qp);
+            const bool sparse = x < S;
+            const bool hit = sparse && (incl > x) && !(excl > x);
+            const double y = x - excl;                 // position inside this lane's entries
+            int k_sel = 0;
+            bool ok;
+            if (n4max <= 1) {
+                const bool b0 = q.s[0] > y, b1 = q.s[1] > y, b2 = q.s[2] > y;
+                k_sel = b0 ? q.k[0] : b1 ? q.k[1] : b2 ? q.k[2] : q.k[3];
+                ok = b0 || b1 || b2 || (q.s[3] > y);
+                if (__ballot(hit && !ok) != 0) {       // rounding left no prefix above the draw:
+                    if (hit && !ok)                    // take the lane's last entry with weight
+                        k_sel = q.s[3] > q.s[2] ? q.k[3] : q.s[2] > q.s[1] ? q.k[2]
+                              : q.s[1] > q.s[0] ? q.k[1] : q.k[0];
+                }
+            } else {
+                ok = false;
+                if (__ballot(hit) != 0) {              // second walk, the hit lane's entries only
+                    double acc = 0.0;
                     int last_k = 0;
-                    for (int base = 0; base < nnz_i; base += kWave) {
-                        const int j = base + lane;
-                        const bool have = j < nnz_i;
-                        int c = 0, k = 0;
-                        if (have) { c = cnt[j]; k = (int)top[j]; }
-                        float w = pstar[k];
-                        if (have && k == o_i) { c -= 1; w = w_o_i; }
-                        const double p1 = (double)c * (double)w;
-                        const double incl = wave_inclusive_sum(p1) + carry;
-                        const uint64_t m = __ballot(incl > x);
-                        if (m != 0) {
-                            z_sparse = read_lane(k, __ffsll((unsigned long long)m) - 1);
-                            break;
+                    for (int c = 0; c < n4max; ++c) {
+                        const int e = e0 + 4 * c;
+                        q = row_quad(cnt, top, e, hit && c < n4 && e < nnz, K, r.o, r.w_o, pstar, acc);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const double before = (j == 0) ? acc : q.s[j - 1];
+                            if (!ok && q.s[j] > y) { k_sel = q.k[j]; ok = true; }
+                            if (q.s[j] > before) last_k = q.k[j];
                         }
-                        const uint64_t mp = __ballot(p1 > 0.0);
-                        if (mp != 0) last_k = read_lane(k, 63 - __clzll((unsigned long long)mp));
-                        carry = read_lane(incl, kWave - 1);
+                        acc = q.s[3];
                     }
-                    if (z_sparse < 0) z_sparse = last_k;   // rounding left no prefix above x
+                    if (!ok) k_sel = last_k;
                 }
             }
-            if (lane == i) { S_mine = S; z_new = z_sparse; }
+            if (hit) my_res[ti] = k_sel;
+            if (row_on && !sparse && sl == 0) {
+                my_res[ti] = -1;                        // the draw falls into the dense bucket
+                my_y[ti] = x - S;
+            }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // ---- one token per lane again: dense bucket, store
         if (valid) {
-            if (z_new < 0) {
-                const double x = u * (S_mine + Qp);
-                z_new = dense_bucket_search(pstar, cp, K, ng, a.alpha, x - S_mine, o, w_o, delta);
-            }
+            int z_new = my_res[lane];
+            if (z_new < 0)
+                z_new = dense_bucket_search(pstar, cp, K, ng, a.alpha, my_y[lane], mine.o, mine.w_o,
+                                            delta);
             a.z_next[pos] = (uint16_t)z_new;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

@@ -261,8 +261,9 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     HIP_TRY(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-    const int32_t Kpad = (K + mlda::kGroup - 1) / mlda::kGroup * mlda::kGroup;
-    const size_t sample_lds = (size_t)Kpad * 4 + (size_t)(Kpad / mlda::kGroup) * 8;
+    // one zero entry of p* past the last topic: padding entries of theta rows point at it
+    const int32_t Kpad = (K + mlda::kGroup) / mlda::kGroup * mlda::kGroup;
+    const size_t sample_lds = mlda::sample_lds_bytes(Kpad, kSampleWaves);
     if (sample_lds > (size_t)lds_limit)
         return fail(MLDA_ENOTSUP, "K = " + std::to_string(K) + " needs " + std::to_string(sample_lds) +
                                       " bytes of LDS per workgroup, the device allows " +
