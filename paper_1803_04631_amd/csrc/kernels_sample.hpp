@@ -139,6 +139,110 @@ __device__ __forceinline__ Quad row_quad(const int32_t* cnt, const uint16_t* top
     return q;
 }
 
+// What the 16 lanes of a row need of their token, and where the result goes.
+struct RowCtx {
+    const int32_t* cnt;     // the theta row: counts, then topics
+    const uint16_t* top;
+    int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
+    int o;
+    float w_o;
+    double u, Qp;
+    bool row_on;
+    int ti;                 // token index inside the wave's batch
+};
+
+// Row total S (Eq. 7), the draw x = u (S + Q'), and whether this lane's entries hold it.
+struct RowDraw {
+    double S, x, y;         // y = x - (sum of the lanes before this one)
+    bool sparse, hit;
+};
+
+__device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, int lane) {
+    RowDraw d;
+    const double incl = row_inclusive_sum(lane_sum);
+    const double excl = row_move0<0x111>(incl);
+    d.S = __shfl(incl, lane | (kRowLanes - 1), kWave);
+    d.x = r.u * (d.S + r.Qp);
+    d.sparse = d.x < d.S;
+    d.hit = d.sparse && (incl > d.x) && !(excl > d.x);
+    d.y = d.x - excl;
+    return d;
+}
+
+__device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int k_sel, int sl,
+                                          int* my_res, double* my_y) {
+    if (d.hit) my_res[r.ti] = k_sel;
+    if (r.row_on && !d.sparse && sl == 0) {
+        my_res[r.ti] = -1;                  // the draw falls into the dense bucket p2
+        my_y[r.ti] = d.x - d.S;
+    }
+}
+
+// Rows of at most 64 kQuads entries: every lane keeps its prefix sums in registers.
+template <int kQuads>
+__device__ __forceinline__ void row_pass_kept(const RowCtx& r, int K, const float* pstar, int sl,
+                                              int lane, int* my_res, double* my_y) {
+    Quad q[kQuads];
+    const int e0 = sl * 4 * r.n4;
+    double acc = 0.0;
+#pragma unroll
+    for (int c = 0; c < kQuads; ++c) {
+        const int e = e0 + 4 * c;
+        q[c] = row_quad(r.cnt, r.top, e, c < r.n4 && e < r.nnz, K, r.o, r.w_o, pstar, acc);
+        acc = q[c].s[3];
+    }
+    const RowDraw d = row_draw(acc, r, lane);
+    // smallest entry whose prefix exceeds y (the prefixes never decrease)
+    int k_sel = q[kQuads - 1].k[3];
+#pragma unroll
+    for (int i = 4 * kQuads - 2; i >= 0; --i)
+        if (q[i / 4].s[i % 4] > d.y) k_sel = q[i / 4].k[i % 4];
+    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no prefix above the draw:
+        if (d.hit && !(acc > d.y)) {                 // take the lane's last entry with weight
+            double before = 0.0;
+#pragma unroll
+            for (int i = 0; i < 4 * kQuads; ++i) {
+                if (q[i / 4].s[i % 4] > before) k_sel = q[i / 4].k[i % 4];
+                before = q[i / 4].s[i % 4];
+            }
+        }
+    }
+    row_store(r, d, k_sel, sl, my_res, my_y);
+}
+
+// Longer rows: one walk for the sums, a second one over the hit lane's entries.
+__device__ __forceinline__ void row_pass_long(const RowCtx& r, int n4max, int K, const float* pstar,
+                                              int sl, int lane, int* my_res, double* my_y) {
+    const int e0 = sl * 4 * r.n4;
+    double acc = 0.0;
+    for (int c = 0; c < n4max; ++c) {
+        const int e = e0 + 4 * c;
+        const Quad q = row_quad(r.cnt, r.top, e, c < r.n4 && e < r.nnz, K, r.o, r.w_o, pstar, acc);
+        acc = q.s[3];
+    }
+    const RowDraw d = row_draw(acc, r, lane);
+    int k_sel = 0;
+    if (__ballot(d.hit) != 0) {
+        bool ok = false;
+        int last_k = 0;
+        acc = 0.0;
+        for (int c = 0; c < n4max; ++c) {
+            const int e = e0 + 4 * c;
+            const Quad q = row_quad(r.cnt, r.top, e, d.hit && c < r.n4 && e < r.nnz, K, r.o, r.w_o,
+                                    pstar, acc);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double before = (j == 0) ? acc : q.s[j - 1];
+                if (!ok && q.s[j] > d.y) { k_sel = q.k[j]; ok = true; }
+                if (q.s[j] > before) last_k = q.k[j];
+            }
+            acc = q.s[3];
+        }
+        if (!ok) k_sel = last_k;
+    }
+    row_store(r, d, k_sel, sl, my_res, my_y);
+}
+
 template <int kWaves>
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -214,73 +318,21 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // ---- one token per row of 16 lanes, four tokens per pass
         const int n_here = min(kWave, tl.count - b * kWave);
         for (int p = 0; p * kRowsPerWave < n_here; ++p) {
-            const int ti = p * kRowsPerWave + row;
-            const bool row_on = ti < n_here;
-            const TokenRec r = my_rec[row_on ? ti : 0];
-            const int nnz = row_on ? r.nnz : 0;
-            const int n4 = (nnz + 4 * kRowLanes - 1) / (4 * kRowLanes);   // quads per lane
-            const int n4max = max(max(read_lane(n4, 0), read_lane(n4, 16)),
-                                  max(read_lane(n4, 32), read_lane(n4, 48)));
-            const int32_t* cnt = reinterpret_cast<const int32_t*>(a.slots + (size_t)r.off * 16u);
-            const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz + 3) & ~3));
-            const int e0 = sl * 4 * n4;                 // this lane owns entries e0 .. e0+4*n4-1
-
-            Quad q;
-            double mine_sum;
-            if (n4max <= 1) {
-                q = row_quad(cnt, top, e0, e0 < nnz, K, r.o, r.w_o, pstar, 0.0);
-                mine_sum = q.s[3];
-            } else {
-                double acc = 0.0;
-                for (int c = 0; c < n4max; ++c) {
-                    const int e = e0 + 4 * c;
-                    q = row_quad(cnt, top, e, c < n4 && e < nnz, K, r.o, r.w_o, pstar, acc);
-                    acc = q.s[3];
-                }
-                mine_sum = acc;
-            }
-            const double incl = row_inclusive_sum(mine_sum);
-            const double excl = row_move0<0x111>(incl);                    // lanes before this one
-            const double S = __shfl(incl, lane | (kRowLanes - 1), kWave);  // Eq. 7, row total
-            const double x = r.u * (S + r.Qp);
-            const bool sparse = x < S;
-            const bool hit = sparse && (incl > x) && !(excl > x);
-            const double y = x - excl;                 // position inside this lane's entries
-            int k_sel = 0;
-            bool ok;
-            if (n4max <= 1) {
-                const bool b0 = q.s[0] > y, b1 = q.s[1] > y, b2 = q.s[2] > y;
-                k_sel = b0 ? q.k[0] : b1 ? q.k[1] : b2 ? q.k[2] : q.k[3];
-                ok = b0 || b1 || b2 || (q.s[3] > y);
-                if (__ballot(hit && !ok) != 0) {       // rounding left no prefix above the draw:
-                    if (hit && !ok)                    // take the lane's last entry with weight
-                        k_sel = q.s[3] > q.s[2] ? q.k[3] : q.s[2] > q.s[1] ? q.k[2]
-                              : q.s[1] > q.s[0] ? q.k[1] : q.k[0];
-                }
-            } else {
-                ok = false;
-                if (__ballot(hit) != 0) {              // second walk, the hit lane's entries only
-                    double acc = 0.0;
-                    int last_k = 0;
-                    for (int c = 0; c < n4max; ++c) {
-                        const int e = e0 + 4 * c;
-                        q = row_quad(cnt, top, e, hit && c < n4 && e < nnz, K, r.o, r.w_o, pstar, acc);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const double before = (j == 0) ? acc : q.s[j - 1];
-                            if (!ok && q.s[j] > y) { k_sel = q.k[j]; ok = true; }
-                            if (q.s[j] > before) last_k = q.k[j];
-                        }
-                        acc = q.s[3];
-                    }
-                    if (!ok) k_sel = last_k;
-                }
-            }
-            if (hit) my_res[ti] = k_sel;
-            if (row_on && !sparse && sl == 0) {
-                my_res[ti] = -1;                        // the draw falls into the dense bucket
-                my_y[ti] = x - S;
-            }
+            RowCtx r;
+            r.ti = p * kRowsPerWave + row;
+            r.row_on = r.ti < n_here;
+            const TokenRec rec = my_rec[r.row_on ? r.ti : 0];
+            r.nnz = r.row_on ? rec.nnz : 0;
+            r.n4 = (r.nnz + 4 * kRowLanes - 1) / (4 * kRowLanes);
+            r.o = rec.o; r.w_o = rec.w_o; r.u = rec.u; r.Qp = rec.Qp;
+            r.cnt = reinterpret_cast<const int32_t*>(a.slots + (size_t)rec.off * 16u);
+            r.top = reinterpret_cast<const uint16_t*>(r.cnt + ((r.nnz + 3) & ~3));
+            const int n4max = max(max(read_lane(r.n4, 0), read_lane(r.n4, 16)),
+                                  max(read_lane(r.n4, 32), read_lane(r.n4, 48)));
+            if (n4max <= 1)      row_pass_kept<1>(r, K, pstar, sl, lane, my_res, my_y);
+            else if (n4max <= 2) row_pass_kept<2>(r, K, pstar, sl, lane, my_res, my_y);
+            else if (n4max <= 4) row_pass_kept<4>(r, K, pstar, sl, lane, my_res, my_y);
+            else                 row_pass_long(r, n4max, K, pstar, sl, lane, my_res, my_y);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
