@@ -22,8 +22,9 @@ __global__ void zero_rows_kernel(const int32_t* words, int32_t* n_wk, int32_t K)
 }
 
 // Update phi (Section 6.2: word by word, atomics with good locality): a workgroup
-// histograms one tile's assignments in LDS, then stores the word's row outright if the
-// tile is the whole word, else adds its non-zero bins to the row.
+// histograms one segment (up to 16384 consecutive tokens of one word) in LDS, then stores
+// the word's row outright if the segment is the whole word, else adds its non-zero bins
+// to the row.
 __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* tiles, const uint16_t* z,
                                                        int32_t* n_wk, int32_t K) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -151,16 +152,32 @@ __device__ __forceinline__ void block_partial_store(double v, double* partial) {
     }
 }
 
+// lgG(c + a) - lgG(a) for the small integer counts that make up almost all cells, from a
+// table each workgroup fills in LDS; larger counts call lgamma directly.
+constexpr int kLgTable = 1024;
+
+__device__ __forceinline__ void fill_lg_table(double* table, double a, double lg_a) {
+    for (int c = (int)threadIdx.x; c < kLgTable; c += (int)blockDim.x)
+        table[c] = lgamma((double)c + a) - lg_a;
+    __syncthreads();
+}
+
+__device__ __forceinline__ double lg_rise(const double* table, int c, double a, double lg_a) {
+    return c < kLgTable ? table[c] : lgamma((double)c + a) - lg_a;
+}
+
 __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_wk, int64_t n_cells,
                                                                const int32_t* n_k, int32_t K,
                                                                double beta, double v_beta,
                                                                double* partial) {
+    __shared__ double table[kLgTable];
     const double lg_beta = lgamma(beta);
+    fill_lg_table(table, beta, lg_beta);
     double acc = 0.0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_cells; i += stride) {
         const int c = n_wk[i];
-        if (c > 0) acc += lgamma((double)c + beta) - lg_beta;
+        if (c > 0) acc += lg_rise(table, c, beta, lg_beta);
     }
     if (blockIdx.x == 0) {
         const double lg_vb = lgamma(v_beta);
@@ -170,13 +187,16 @@ __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_
     block_partial_store(acc, partial);
 }
 
-// One wave per document at a time (4 waves per workgroup, persistent).
+// Entries of the theta rows: one wave per document at a time (4 waves per workgroup,
+// persistent).  The per-document term lgG(K alpha) - lgG(N_d + K alpha): one thread each.
 __global__ __launch_bounds__(256) void loglik_doc_side_kernel(const int32_t* doc_ptr,
                                                               const uint2* row_rec,
                                                               const unsigned char* slots,
                                                               int64_t D, double alpha,
                                                               double k_alpha, double* partial) {
+    __shared__ double table[kLgTable];
     const double lg_alpha = lgamma(alpha), lg_ka = lgamma(k_alpha);
+    fill_lg_table(table, alpha, lg_alpha);
     const int lane = lane_id();
     const int64_t wave_global = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
@@ -184,11 +204,11 @@ __global__ __launch_bounds__(256) void loglik_doc_side_kernel(const int32_t* doc
     for (int64_t d = wave_global; d < D; d += n_waves) {
         const uint2 rec = row_rec[d];
         const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)rec.x * 16u);
-        for (int j = lane; j < (int)rec.y; j += kWave)
-            acc += lgamma((double)cnt[j] + alpha) - lg_alpha;
-        if (lane == 0)
-            acc += lg_ka - lgamma((double)(doc_ptr[d + 1] - doc_ptr[d]) + k_alpha);
+        for (int j = lane; j < (int)rec.y; j += kWave) acc += lg_rise(table, cnt[j], alpha, lg_alpha);
     }
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; d < D; d += stride)
+        acc += lg_ka - lgamma((double)(doc_ptr[d + 1] - doc_ptr[d]) + k_alpha);
     block_partial_store(acc, partial);
 }
 

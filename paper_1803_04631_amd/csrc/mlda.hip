@@ -45,6 +45,7 @@ constexpr int kMaxTimedIters = 1024;
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
+constexpr int kPhiSegment = 16384;    // tokens one workgroup histograms for the phi rebuild
 
 size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
     return align_up((size_t)(((cap + 3) & ~(int64_t)3) * 6), kSlotAlign);
@@ -52,11 +53,11 @@ size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
 
 // Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
 struct Layout {
-    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, row_rec, slots, n_wk, n_k, tiles, split,
+    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, row_rec, slots, n_wk, n_k, tiles, segs, split,
         ll_partial, ll_value, row_entries, total;
     void finish() {
         size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &row_rec, &slots,
-                           &n_wk, &n_k, &tiles, &split, &ll_partial, &ll_value, &row_entries};
+                           &n_wk, &n_k, &tiles, &segs, &split, &ll_partial, &ll_value, &row_entries};
         total = 0;
         for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
     }
@@ -66,7 +67,7 @@ constexpr int kLoglikBlocks = 2048;
 constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entries (> kMaxTimedIters)
 
 Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
-                  size_t n_split) {
+                  size_t n_segs, size_t n_split) {
     Layout L{};
     L.tok_doc = (size_t)T * 4;
     L.tok_id = (size_t)T * 4;
@@ -79,6 +80,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
     L.n_wk = (size_t)V * (size_t)K * 4;
     L.n_k = (size_t)K * 4;
     L.tiles = n_tiles * sizeof(mlda::Tile);
+    L.segs = n_segs * sizeof(mlda::Tile);
     L.split = n_split * 4;
     L.ll_partial = (size_t)2 * kLoglikBlocks * 8;
     L.ll_value = 8;
@@ -91,7 +93,8 @@ Layout layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
     const size_t tile = (size_t)tile_tokens_for(K);
     const size_t slots = (size_t)T * 6 + (size_t)D * (18 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
-    return layout_for(D, T, V, K, slots, n_tiles, (size_t)V);
+    const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
+    return layout_for(D, T, V, K, slots, n_tiles, n_segs, (size_t)V);
 }
 
 template <class F>
@@ -120,8 +123,9 @@ struct mlda_ctx {
     uint2* row_rec = nullptr;
     unsigned char* slots = nullptr;
     size_t slots_bytes = 0;
-    mlda::Tile* tiles = nullptr;
-    int32_t n_tiles = 0, n_split = 0;
+    mlda::Tile* tiles = nullptr;        // sampling tiles
+    mlda::Tile* segs = nullptr;         // phi rebuild segments
+    int32_t n_tiles = 0, n_segs = 0, n_split = 0;
     double *ll_partial = nullptr, *ll_value = nullptr;
     unsigned long long* row_entries = nullptr;   // ring: [r % kEntryRing] written by rebuild r
     int64_t rebuilds = 0;                        // rebuilds launched so far
@@ -158,8 +162,8 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
     hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream, c->n_k,
                        (int64_t)c->K, 0);
     if (c->n_tiles > 0) {
-        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_tiles), dim3(256), hist_bytes,
-                           c->stream, c->tiles, z, c->n_wk, c->K);
+        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes,
+                           c->stream, c->segs, z, c->n_wk, c->K);
         const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
         hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes,
                            c->stream, z, c->T, c->n_k, c->K);
@@ -269,20 +273,52 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                                       " bytes of LDS per workgroup, the device allows " +
                                       std::to_string(lds_limit));
 
-    // ---- word-first order (stable counting sort over chunks of the token range)
+    // ---- word-first order (Section 6.1.2).  Inside a word the tokens are put in order of
+    // falling document length, so that the four theta rows a wave walks together have
+    // similar lengths; any order inside a word gives the same result, because the uniforms
+    // are keyed by the caller's token index.  Stable counting sort by word over chunks of
+    // the length-sorted document sequence.
+    std::vector<int32_t> doc_order;
+    std::vector<int64_t> order_tokens;           // tokens before each position of doc_order
+    try {
+        doc_order.resize((size_t)D);
+        order_tokens.resize((size_t)D + 1);
+        int64_t max_len = 0;
+        for (int64_t d = 0; d < D; ++d) max_len = std::max(max_len, doc_ptr[d + 1] - doc_ptr[d]);
+        std::vector<int64_t> len_start((size_t)max_len + 2, 0);
+        for (int64_t d = 0; d < D; ++d) ++len_start[(size_t)(max_len - (doc_ptr[d + 1] - doc_ptr[d])) + 1];
+        for (int64_t l = 0; l <= max_len; ++l) len_start[(size_t)l + 1] += len_start[(size_t)l];
+        for (int64_t d = 0; d < D; ++d)
+            doc_order[(size_t)len_start[(size_t)(max_len - (doc_ptr[d + 1] - doc_ptr[d]))]++] = (int32_t)d;
+        order_tokens[0] = 0;
+        for (int64_t i = 0; i < D; ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            order_tokens[(size_t)i + 1] = order_tokens[(size_t)i] + (doc_ptr[d + 1] - doc_ptr[d]);
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
     const int n_chunks = (int)std::max<int64_t>(
         1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 32, T / 65536 + 1}));
     std::vector<std::vector<int32_t>> chunk_hist(n_chunks);
     std::vector<int> chunk_bad(n_chunks, 0);
-    auto chunk_lo = [&](int c) { return T / n_chunks * c + std::min<int64_t>(c, T % n_chunks); };
+    // chunk c holds the documents doc_order[chunk_lo(c) .. chunk_lo(c+1)), about T/n_chunks tokens
+    auto chunk_lo = [&](int c) -> int64_t {
+        if (c >= n_chunks) return D;
+        const int64_t want = T / n_chunks * c;
+        return std::lower_bound(order_tokens.begin(), order_tokens.end(), want) - order_tokens.begin();
+    };
     try {
         parallel_chunks(n_chunks, [&](int c) {
             auto& h = chunk_hist[c];
             h.assign((size_t)V, 0);
-            for (int64_t t = chunk_lo(c); t < chunk_lo(c + 1); ++t) {
-                const int32_t w = word_ids[t];
-                if (w < 0 || w >= V) { chunk_bad[c] = 1; return; }
-                ++h[w];
+            for (int64_t i = chunk_lo(c); i < chunk_lo(c + 1); ++i) {
+                const int64_t d = doc_order[(size_t)i];
+                for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; ++t) {
+                    const int32_t w = word_ids[t];
+                    if (w < 0 || w >= V) { chunk_bad[c] = 1; return; }
+                    ++h[w];
+                }
             }
         });
     } catch (const std::bad_alloc&) {
@@ -293,7 +329,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
 
     std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_doc, tok_id, doc_map, doc_ptr32, split_words;
     std::vector<uint2> row_rec;
-    std::vector<mlda::Tile> tiles;
+    std::vector<mlda::Tile> tiles, segs;
     size_t slots_bytes = 0;
     try {
         for (int32_t v = 0; v < V; ++v) {
@@ -310,15 +346,15 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         doc_map.resize((size_t)T);
         parallel_chunks(n_chunks, [&](int c) {
             auto& start = chunk_hist[c];
-            const int64_t lo = chunk_lo(c), hi = chunk_lo(c + 1);
-            int64_t d = std::upper_bound(doc_ptr, doc_ptr + D + 1, lo) - doc_ptr - 1;
-            for (int64_t t = lo; t < hi; ++t) {
-                while (doc_ptr[d + 1] <= t) ++d;
-                const int32_t w = word_ids[t];
-                const int32_t pos = word_ptr[w] + start[w]++;
-                tok_id[pos] = (int32_t)t;
-                tok_doc[pos] = (int32_t)d;
-                doc_map[t] = pos;
+            for (int64_t i = chunk_lo(c); i < chunk_lo(c + 1); ++i) {
+                const int64_t d = doc_order[(size_t)i];
+                for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; ++t) {
+                    const int32_t w = word_ids[t];
+                    const int32_t pos = word_ptr[w] + start[w]++;
+                    tok_id[pos] = (int32_t)t;
+                    tok_doc[pos] = (int32_t)d;
+                    doc_map[t] = pos;
+                }
             }
         });
         chunk_hist.clear();
@@ -337,17 +373,21 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         const int32_t tile = tile_tokens_for(K);
         for (int32_t v = 0; v < V; ++v) {
             const int32_t n = word_ptr[v + 1] - word_ptr[v];
-            if (n > tile) split_words.push_back(v);
             for (int32_t b = 0; b < n; b += tile)
                 tiles.push_back(mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), n <= tile ? 1 : 0});
+            if (n > kPhiSegment) split_words.push_back(v);
+            for (int32_t b = 0; b < n; b += kPhiSegment)
+                segs.push_back(mlda::Tile{v, word_ptr[v] + b, std::min(kPhiSegment, n - b),
+                                          n <= kPhiSegment ? 1 : 0});
         }
-        std::stable_sort(tiles.begin(), tiles.end(),
-                         [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
+        auto larger_first = [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; };
+        std::stable_sort(tiles.begin(), tiles.end(), larger_first);
+        std::stable_sort(segs.begin(), segs.end(), larger_first);
     } catch (const std::bad_alloc&) {
         return fail(MLDA_ENOMEM, "out of host memory");
     }
 
-    const Layout L = layout_for(D, T, V, K, slots_bytes, tiles.size(), split_words.size());
+    const Layout L = layout_for(D, T, V, K, slots_bytes, tiles.size(), segs.size(), split_words.size());
     if (L.total > workspace_bytes)
         return fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
                                      std::to_string(L.total));
@@ -359,6 +399,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->stream = (hipStream_t)hip_stream;
     c->n_cus = n_cus; c->lds_limit = lds_limit; c->sample_lds = sample_lds;
     c->n_tiles = (int32_t)tiles.size();
+    c->n_segs = (int32_t)segs.size();
     c->n_split = (int32_t)split_words.size();
     c->slots_bytes = slots_bytes;
     c->doc_ptr_host.assign(doc_ptr, doc_ptr + D + 1);
@@ -376,6 +417,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->n_wk = (int32_t*)take(L.n_wk);
     c->n_k = (int32_t*)take(L.n_k);
     c->tiles = (mlda::Tile*)take(L.tiles);
+    c->segs = (mlda::Tile*)take(L.segs);
     c->split_words = (int32_t*)take(L.split);
     c->ll_partial = (double*)take(L.ll_partial);
     c->ll_value = (double*)take(L.ll_value);
@@ -392,6 +434,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
     if (e == hipSuccess) e = up(c->row_rec, row_rec.data(), (size_t)D * 8);
     if (e == hipSuccess) e = up(c->tiles, tiles.data(), tiles.size() * sizeof(mlda::Tile));
+    if (e == hipSuccess) e = up(c->segs, segs.data(), segs.size() * sizeof(mlda::Tile));
     if (e == hipSuccess) e = up(c->split_words, split_words.data(), split_words.size() * 4);
     if (e == hipSuccess) {
         // rows of words without tokens are never written again: start phi at zero
