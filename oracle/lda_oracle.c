@@ -81,6 +81,7 @@ void oracle_uniforms(uint64_t seed, uint32_t iter, uint64_t token0, int64_t n, d
 
 /* "Initially, each token is randomly assigned with a topic" (Section 2.1). */
 void oracle_init_topics(int64_t T, int32_t K, uint64_t seed, uint16_t* z) {
+#pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; ++t) {
         int32_t k = (int32_t)(oracle_uniform(seed, 0u, (uint64_t)t) * (double)K);
         if (k > K - 1) k = K - 1;
