@@ -27,6 +27,17 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES = {}
 
 
+def paper_unshared_accounting(k_d, k, int_bytes=4, float_bytes=4):
+    """The paper's Table 1: flops and bytes per token of the four sampler steps when nothing
+    is shared between samplers (32-bit integers and floats).  Returns {step: (flops, bytes)}."""
+    return {
+        "compute_S": (4 * k_d, 3 * int_bytes * k_d),
+        "compute_Q": (2 * k, 2 * int_bytes * k),
+        "sample_p1": (6 * k_d, (3 * int_bytes + 2 * float_bytes) * k_d),
+        "sample_p2": (3 * k, (2 * int_bytes + 2 * float_bytes) * k),
+    }
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 

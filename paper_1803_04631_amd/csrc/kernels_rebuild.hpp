@@ -14,7 +14,7 @@ __global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
-// Rows of words whose tokens span several tiles are accumulated with atomics and must
+// Rows of words whose tokens span several segments are accumulated with atomics and must
 // start at zero.  grid = (#split words, ceil(K / blockDim)).
 __global__ void zero_rows_kernel(const int32_t* words, int32_t* n_wk, int32_t K) {
     const int k = (int)(blockIdx.y * blockDim.x + threadIdx.x);
@@ -25,11 +25,11 @@ __global__ void zero_rows_kernel(const int32_t* words, int32_t* n_wk, int32_t K)
 // histograms one segment (up to 16384 consecutive tokens of one word) in LDS, then stores
 // the word's row outright if the segment is the whole word, else adds its non-zero bins
 // to the row.
-__global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* tiles, const uint16_t* z,
+__global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const uint16_t* z,
                                                        int32_t* n_wk, int32_t K) {
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* hist = reinterpret_cast<int32_t*>(lds);
-    const Tile tl = tiles[blockIdx.x];
+    const Tile tl = segs[blockIdx.x];
     const int tid = (int)threadIdx.x;
     for (int k = tid; k < K; k += 256) hist[k] = 0;
     __syncthreads();
@@ -65,75 +65,7 @@ __global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, in
     }
 }
 
-// Update theta (Section 6.2): document by document, (1) a dense K-long histogram of the
-// document's assignments, reached through the document->token map, (2) compaction of the
-// non-zero bins into the row (topics ascending).  One wave per document, persistent; the
-// dense row lives in LDS and is left all-zero for the next document.  Row layout:
-// int32 counts[round4(nnz)] then uint16 topics[round4(nnz)]; padding entries hold count 0
-// and topic K.
-__global__ __launch_bounds__(kWave) void theta_rows_kernel(const int32_t* doc_ptr,
-                                                           const int32_t* doc_map,
-                                                           const uint16_t* z, uint2* row_rec,
-                                                           unsigned char* slots, int64_t D,
-                                                           int32_t K,
-                                                           unsigned long long* row_entries) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    int32_t* hist = reinterpret_cast<int32_t*>(lds);
-    const int lane = (int)threadIdx.x;
-    for (int k = lane; k < K; k += kWave) hist[k] = 0;
-    __syncthreads();
-    unsigned long long visited = 0;      // sum of N_d * nnz_d over this wave's documents
-    for (int64_t d = blockIdx.x; d < D; d += gridDim.x) {
-        const int b = doc_ptr[d], n = doc_ptr[d + 1] - b;
-        int fresh = 0;
-        for (int i = lane; i < n; i += kWave) {
-            const int k = (int)z[doc_map[b + i]];
-            fresh += (atomicAdd(&hist[k], 1) == 0) ? 1 : 0;     // first token of a topic
-        }
-        const int nnz = wave_sum(fresh);
-        __syncthreads();
-        const int nnz_pad = (nnz + 3) & ~3;
-        const uint32_t off = row_rec[d].x;
-        int32_t* cnt = reinterpret_cast<int32_t*>(slots + (size_t)off * 16u);
-        uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
-        int filled = 0;
-        for (int base = 0; base < K; base += kWave) {
-            const int k = base + lane;
-            const int c = (k < K) ? hist[k] : 0;
-            const uint64_t m = __ballot(c > 0);
-            if (m == 0) continue;
-            if (c > 0) {
-                const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
-                cnt[at] = c;
-                top[at] = (uint16_t)k;
-                hist[k] = 0;
-            }
-            filled += __popcll((unsigned long long)m);
-        }
-        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
-        if (lane == 0) row_rec[d].y = (uint32_t)nnz;
-        visited += (unsigned long long)n * (unsigned long long)nnz;
-        __syncthreads();
-    }
-    // row entries the next sampling pass will read: one row walk per token
-    if (lane == 0 && visited != 0) atomicAdd(row_entries, visited);
-}
-
-// Boundary order changes.  doc_map[t] = word-major position of document-major token t;
-// tok_id[pos] = document-major index of word-major position pos.
-__global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,
-                                    uint16_t* z_doc, int64_t T) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < T) z_doc[t] = z_word[doc_map[t]];
-}
-
-__global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_id,
-                                     uint16_t* z_word, int64_t T) {
-    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pos < T) z_word[pos] = z_doc[tok_id[pos]];
-}
-
-// ------------------------------------------------------------------ log-likelihood
+// ------------------------------------------------------------------ log-likelihood helpers
 // log p(w,z) = sum_k [lgG(V beta) - lgG(n_k + V beta)] + sum_{v,k} [lgG(n_wk + beta) - lgG(beta)]
 //            + sum_d [lgG(K alpha) - lgG(N_d + K alpha)] + sum_{d,k} [lgG(n_dk + alpha) - lgG(alpha)]
 // Each workgroup writes one fp64 partial; a last single-workgroup kernel adds them in a
@@ -166,6 +98,143 @@ __device__ __forceinline__ double lg_rise(const double* table, int c, double a, 
     return c < kLgTable ? table[c] : lgamma((double)c + a) - lg_a;
 }
 
+// The same table in global memory (kLgTable entries, then lgG(a) itself), filled once per
+// context: lets a register-lean kernel avoid lgamma altogether.
+__global__ void lg_table_kernel(double* table, double a) {
+    const double lg_a = lgamma(a);
+    const int c = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (c < kLgTable) table[c] = lgamma((double)c + a) - lg_a;
+    if (c == kLgTable) table[c] = lg_a;
+}
+
+// lgG(x) for x >= 1024 by Stirling's series; the first omitted term is below 1e-24.
+__device__ __forceinline__ double lgamma_large(double x) {
+    const double r = 1.0 / x, r2 = r * r;
+    return (x - 0.5) * log(x) - x + 0.91893853320467274178 +
+           r * (1.0 / 12.0 - r2 * (1.0 / 360.0 - r2 * (1.0 / 1260.0)));
+}
+
+// Counts of a theta row are small: the rebuild keeps only this many table entries in LDS
+// (occupancy matters more there) and reads the rest of the table from global memory.
+constexpr int kThetaLgTable = 128;
+
+// One document as the theta rebuild needs it, stored in processing order.
+struct __align__(16) DocRec {
+    int32_t begin;      // first document-major token
+    int32_t n;          // tokens
+    uint32_t slot;      // offset of the theta row's slot, 16-byte units
+    int32_t doc;        // document id
+};
+
+// Word-major position of the document's token `j`, or -1 past its end.
+__device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const DocRec& r, int j) {
+    return j < r.n ? doc_map[r.begin + j] : -1;
+}
+
+// Update theta (Section 6.2): document by document, (1) a dense K-long histogram of the
+// document's assignments, reached through the document->token map, (2) compaction of the
+// non-zero bins into the row (topics ascending).  One wave per document, persistent; the
+// dense row lives in LDS and is left all-zero for the next document.  Documents are taken in
+// the order the tokens have inside a word (falling length), so that documents in flight
+// together gather from neighbouring lines of z.  The walk is a chain of dependent loads
+// (record -> map -> z), so it is software-pipelined: while the current document's topics are
+// gathered, the map entries of the wave's next document and the record of the one after are
+// already on their way.  Row layout: int32 counts[round4(nnz)] then uint16
+// topics[round4(nnz)]; padding entries hold count 0 and topic K.
+// While the counts pass through registers the kernel also adds up the theta entries' term of
+// the log-likelihood, sum_{d,k} lgG(n_dk + alpha) - lgG(alpha), one partial per workgroup.
+__global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
+                                                           const int32_t* doc_map,
+                                                           const uint16_t* z, uint2* row_rec,
+                                                           unsigned char* slots, int64_t D,
+                                                           int32_t K, double alpha,
+                                                           const double* lg_table,
+                                                           unsigned long long* row_entries,
+                                                           double* ll_partial) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    int32_t* hist = reinterpret_cast<int32_t*>(lds);
+    double* table = reinterpret_cast<double*>(lds + (((size_t)K * 4 + 15) & ~(size_t)15));
+    const int lane = (int)threadIdx.x;
+    const double lg_alpha = lg_table[kLgTable];
+    for (int k = lane; k < K; k += kWave) hist[k] = 0;
+    for (int c = lane; c < kThetaLgTable; c += kWave) table[c] = lg_table[c];
+    __syncthreads();
+    unsigned long long visited = 0;      // sum of N_d * nnz_d over this wave's documents
+    double ll = 0.0;
+    const int64_t step = gridDim.x;
+    const DocRec none = {0, 0, 0u, 0};
+    int64_t i = blockIdx.x;
+    DocRec cur = i < D ? docs[i] : none;
+    DocRec nxt = i + step < D ? docs[i + step] : none;
+    int p0 = doc_token_position(doc_map, cur, lane);
+    int p1 = doc_token_position(doc_map, cur, lane + kWave);
+    for (; i < D; i += step) {
+        // topics of the current document's first 128 tokens
+        const int k0 = p0 >= 0 ? (int)z[p0] : -1;
+        const int k1 = p1 >= 0 ? (int)z[p1] : -1;
+        // on their way meanwhile: the next document's positions, the record after it
+        const int q0 = doc_token_position(doc_map, nxt, lane);
+        const int q1 = doc_token_position(doc_map, nxt, lane + kWave);
+        const DocRec after = i + 2 * step < D ? docs[i + 2 * step] : none;
+
+        int fresh = 0;                    // first token of a topic
+        if (k0 >= 0) fresh += (atomicAdd(&hist[k0], 1) == 0) ? 1 : 0;
+        if (k1 >= 0) fresh += (atomicAdd(&hist[k1], 1) == 0) ? 1 : 0;
+        for (int j = 2 * kWave + lane; j < cur.n; j += kWave) {
+            const int k = (int)z[doc_map[cur.begin + j]];
+            fresh += (atomicAdd(&hist[k], 1) == 0) ? 1 : 0;
+        }
+        const int nnz = wave_sum(fresh);
+        __syncthreads();
+        const int nnz_pad = (nnz + 3) & ~3;
+        int32_t* cnt = reinterpret_cast<int32_t*>(slots + (size_t)cur.slot * 16u);
+        uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
+        int filled = 0;
+        for (int base = 0; base < K; base += kWave) {
+            const int k = base + lane;
+            const int c = (k < K) ? hist[k] : 0;
+            const uint64_t m = __ballot(c > 0);
+            if (m == 0) continue;
+            if (c > 0) {
+                const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
+                cnt[at] = c;
+                top[at] = (uint16_t)k;
+                hist[k] = 0;
+                if (c < kThetaLgTable) ll += table[c];
+            }
+            if (__ballot(c >= kThetaLgTable) != 0) {  // rare: taken by the whole wave or not at all
+                if (c >= kThetaLgTable)
+                    ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
+            }
+            filled += __popcll((unsigned long long)m);
+        }
+        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
+        if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;
+        visited += (unsigned long long)cur.n * (unsigned long long)nnz;
+        __syncthreads();
+        cur = nxt; nxt = after; p0 = q0; p1 = q1;
+    }
+    // row entries the next sampling pass will read: one row walk per token
+    if (lane == 0 && visited != 0) atomicAdd(row_entries, visited);
+    block_partial_store(ll, ll_partial);
+}
+
+// Boundary order changes.  doc_map[t] = word-major position of document-major token t;
+// tok_id[pos] = document-major index of word-major position pos.
+__global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,
+                                    uint16_t* z_doc, int64_t T) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) z_doc[t] = z_word[doc_map[t]];
+}
+
+__global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_id,
+                                     uint16_t* z_word, int64_t T) {
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos < T) z_word[pos] = z_doc[tok_id[pos]];
+}
+
+// ------------------------------------------------------------------ log-likelihood kernels
+
 __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_wk, int64_t n_cells,
                                                                const int32_t* n_k, int32_t K,
                                                                double beta, double v_beta,
@@ -187,25 +256,12 @@ __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_
     block_partial_store(acc, partial);
 }
 
-// Entries of the theta rows: one wave per document at a time (4 waves per workgroup,
-// persistent).  The per-document term lgG(K alpha) - lgG(N_d + K alpha): one thread each.
-__global__ __launch_bounds__(256) void loglik_doc_side_kernel(const int32_t* doc_ptr,
-                                                              const uint2* row_rec,
-                                                              const unsigned char* slots,
-                                                              int64_t D, double alpha,
+// The per-document term lgG(K alpha) - lgG(N_d + K alpha), one thread per document (the
+// entries of the theta rows are summed by theta_rows_kernel).
+__global__ __launch_bounds__(256) void loglik_doc_term_kernel(const int32_t* doc_ptr, int64_t D,
                                                               double k_alpha, double* partial) {
-    __shared__ double table[kLgTable];
-    const double lg_alpha = lgamma(alpha), lg_ka = lgamma(k_alpha);
-    fill_lg_table(table, alpha, lg_alpha);
-    const int lane = lane_id();
-    const int64_t wave_global = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    const double lg_ka = lgamma(k_alpha);
     double acc = 0.0;
-    for (int64_t d = wave_global; d < D; d += n_waves) {
-        const uint2 rec = row_rec[d];
-        const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)rec.x * 16u);
-        for (int j = lane; j < (int)rec.y; j += kWave) acc += lg_rise(table, cnt[j], alpha, lg_alpha);
-    }
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; d < D; d += stride)
         acc += lg_ka - lgamma((double)(doc_ptr[d + 1] - doc_ptr[d]) + k_alpha);

@@ -53,17 +53,18 @@ size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
 
 // Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
 struct Layout {
-    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, row_rec, slots, n_wk, n_k, tiles, segs, split,
-        ll_partial, ll_value, row_entries, total;
+    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, doc_order, row_rec, slots, n_wk, n_k, tiles, segs, split,
+        ll_partial, ll_value, lg_table, row_entries, total;
     void finish() {
-        size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &row_rec, &slots,
-                           &n_wk, &n_k, &tiles, &segs, &split, &ll_partial, &ll_value, &row_entries};
+        size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &doc_order, &row_rec, &slots,
+                           &n_wk, &n_k, &tiles, &segs, &split, &ll_partial, &ll_value, &lg_table, &row_entries};
         total = 0;
         for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
     }
 };
 
 constexpr int kLoglikBlocks = 2048;
+constexpr int kMaxThetaGrid = 8192;    // workgroups of the theta rebuild (each leaves one likelihood partial)
 constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entries (> kMaxTimedIters)
 
 Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
@@ -75,6 +76,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
     L.z0 = (size_t)T * 2;
     L.z1 = (size_t)T * 2;
     L.doc_ptr = (size_t)(D + 1) * 4;
+    L.doc_order = (size_t)D * sizeof(mlda::DocRec);
     L.row_rec = (size_t)D * 8;
     L.slots = slots_bytes;
     L.n_wk = (size_t)V * (size_t)K * 4;
@@ -82,8 +84,9 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
     L.tiles = n_tiles * sizeof(mlda::Tile);
     L.segs = n_segs * sizeof(mlda::Tile);
     L.split = n_split * 4;
-    L.ll_partial = (size_t)2 * kLoglikBlocks * 8;
+    L.ll_partial = (size_t)(2 * kLoglikBlocks + kMaxThetaGrid) * 8;
     L.ll_value = 8;
+    L.lg_table = (size_t)(mlda::kLgTable + 1) * 8;
     L.row_entries = (size_t)kEntryRing * 8;
     L.finish();
     return L;
@@ -117,6 +120,8 @@ struct mlda_ctx {
     int n_cus = 0, lds_limit = 0;
 
     int32_t *tok_doc = nullptr, *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    mlda::DocRec* doc_order = nullptr;  // documents by falling length, as the theta rebuild walks them
+    int32_t theta_grid = 0;
     int32_t *n_wk = nullptr, *n_k = nullptr, *split_words = nullptr;
     uint16_t* z[2] = {nullptr, nullptr};
     int cur = 0;
@@ -127,6 +132,7 @@ struct mlda_ctx {
     mlda::Tile* segs = nullptr;         // phi rebuild segments
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
     double *ll_partial = nullptr, *ll_value = nullptr;
+    double* lg_table = nullptr;          // lgG(c + alpha) - lgG(alpha), c < 1024, then lgG(alpha)
     unsigned long long* row_entries = nullptr;   // ring: [r % kEntryRing] written by rebuild r
     int64_t rebuilds = 0;                        // rebuilds launched so far
     int32_t last_step_iters = 0;
@@ -170,12 +176,13 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
     }
     if (ev_phi) HIP_TRY(hipEventRecord(*ev_phi, c->stream));
     if (c->D > 0) {
-        const int per_cu = std::max(1, std::min(16, (int)(c->lds_limit / std::max<size_t>(hist_bytes, 1))));
-        const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * per_cu);
+        const size_t theta_lds = ((hist_bytes + 15) & ~(size_t)15) + (size_t)kThetaLgTable * 8;
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
-        hipLaunchKernelGGL(theta_rows_kernel, dim3((unsigned)grid), dim3(kWave), hist_bytes, c->stream,
-                           c->doc_ptr, c->doc_map, z, c->row_rec, c->slots, c->D, c->K, entries);
+        hipLaunchKernelGGL(theta_rows_kernel, dim3((unsigned)c->theta_grid), dim3(kWave), theta_lds,
+                           c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
+                           c->D, c->K, c->alpha, c->lg_table, entries,
+                           c->ll_partial + 2 * kLoglikBlocks);
     }
     c->rebuilds += 1;
     if (ev_theta) HIP_TRY(hipEventRecord(*ev_theta, c->stream));
@@ -187,11 +194,10 @@ int launch_loglik(mlda_ctx* c) {
     const int64_t cells = (int64_t)c->V * c->K;
     hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->n_wk,
                        cells, c->n_k, c->K, c->beta, (double)c->V * c->beta, c->ll_partial);
-    hipLaunchKernelGGL(loglik_doc_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
-                       c->doc_ptr, c->row_rec, c->slots, c->D, c->alpha, (double)c->K * c->alpha,
-                       c->ll_partial + kLoglikBlocks);
+    hipLaunchKernelGGL(loglik_doc_term_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
+                       c->doc_ptr, c->D, (double)c->K * c->alpha, c->ll_partial + kLoglikBlocks);
     hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial,
-                       2 * kLoglikBlocks, c->ll_value);
+                       2 * kLoglikBlocks + c->theta_grid, c->ll_value);
     c->ll_fresh = true;
     return launch_check("log-likelihood kernels");
 }
@@ -329,6 +335,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
 
     std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_doc, tok_id, doc_map, doc_ptr32, split_words;
     std::vector<uint2> row_rec;
+    std::vector<mlda::DocRec> doc_recs;
     std::vector<mlda::Tile> tiles, segs;
     size_t slots_bytes = 0;
     try {
@@ -369,6 +376,13 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
             slots_bytes += slot_bytes_for(cap);
         }
 
+        doc_recs.resize((size_t)D);
+        for (int64_t i = 0; i < D; ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            doc_recs[(size_t)i] = mlda::DocRec{(int32_t)doc_ptr[d], (int32_t)(doc_ptr[d + 1] - doc_ptr[d]),
+                                              row_rec[(size_t)d].x, (int32_t)d};
+        }
+
         // ---- tiles of one word each, largest first (Section 6.1.2)
         const int32_t tile = tile_tokens_for(K);
         for (int32_t v = 0; v < V; ++v) {
@@ -399,6 +413,11 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->stream = (hipStream_t)hip_stream;
     c->n_cus = n_cus; c->lds_limit = lds_limit; c->sample_lds = sample_lds;
     c->n_tiles = (int32_t)tiles.size();
+    {
+        const size_t theta_lds = (((size_t)K * 4 + 15) & ~(size_t)15) + (size_t)mlda::kThetaLgTable * 8;
+        const int per_cu = std::max(1, std::min(24, (int)(144 * 1024 / theta_lds)));
+        c->theta_grid = (int32_t)std::min<int64_t>({D, (int64_t)n_cus * per_cu, (int64_t)kMaxThetaGrid});
+    }
     c->n_segs = (int32_t)segs.size();
     c->n_split = (int32_t)split_words.size();
     c->slots_bytes = slots_bytes;
@@ -412,6 +431,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->z[0] = (uint16_t*)take(L.z0);
     c->z[1] = (uint16_t*)take(L.z1);
     c->doc_ptr = (int32_t*)take(L.doc_ptr);
+    c->doc_order = (mlda::DocRec*)take(L.doc_order);
     c->row_rec = (uint2*)take(L.row_rec);
     c->slots = take(L.slots);
     c->n_wk = (int32_t*)take(L.n_wk);
@@ -421,6 +441,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->split_words = (int32_t*)take(L.split);
     c->ll_partial = (double*)take(L.ll_partial);
     c->ll_value = (double*)take(L.ll_value);
+    c->lg_table = (double*)take(L.lg_table);
     c->row_entries = (unsigned long long*)take(L.row_entries);
 
     auto up = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
@@ -432,11 +453,14 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     if (e == hipSuccess) e = up(c->tok_id, tok_id.data(), (size_t)T * 4);
     if (e == hipSuccess) e = up(c->doc_map, doc_map.data(), (size_t)T * 4);
     if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
+    if (e == hipSuccess) e = up(c->doc_order, doc_recs.data(), (size_t)D * sizeof(mlda::DocRec));
     if (e == hipSuccess) e = up(c->row_rec, row_rec.data(), (size_t)D * 8);
     if (e == hipSuccess) e = up(c->tiles, tiles.data(), tiles.size() * sizeof(mlda::Tile));
     if (e == hipSuccess) e = up(c->segs, segs.data(), segs.size() * sizeof(mlda::Tile));
     if (e == hipSuccess) e = up(c->split_words, split_words.data(), split_words.size() * 4);
     if (e == hipSuccess) {
+        hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
+                           c->stream, c->lg_table, alpha);
         // rows of words without tokens are never written again: start phi at zero
         const int64_t cells = (int64_t)V * K;
         hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
@@ -454,7 +478,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void*)mlda::theta_rows_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    K * 4 + 16 + mlda::kThetaLgTable * 8);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
