@@ -17,7 +17,9 @@
 //     load, accumulates them in fp64, and a 4-step in-row DPP scan gives the prefix over
 //     lanes.  The lane whose range holds the draw finds "the smallest k whose prefix exceeds
 //     it" (Section 6.1.1) among its own entries.  Token parameters and results travel
-//     between the per-lane and per-row phases through small per-wave LDS records.
+//     between the per-lane and per-row phases through small per-wave LDS records;
+//   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
+//     loads of the next four rows are issued before the current four are worked on.
 #pragma once
 #include "device_util.hpp"
 
@@ -51,6 +53,7 @@ struct SampleArgs {
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
 constexpr int kRowLanes = 16;   // lanes that walk one token's theta row (one DPP row)
 constexpr int kRowsPerWave = kWave / kRowLanes;
+constexpr int kAheadQuads = 2;  // quads per lane whose loads are issued one pass ahead
 
 struct __align__(16) TokenRec { // per-lane phase -> per-row phase, 32 bytes
     uint32_t off;               // slot offset of the token's theta row, 16-byte units
@@ -109,25 +112,55 @@ __device__ __forceinline__ double row_inclusive_sum(double v) {
     return v;
 }
 
-// Four entries of a theta row owned by one lane: p1 = (count - [k = o]) * p*'(k), Eq. 6,
-// accumulated onto `base`.  s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
+// What the 16 lanes of a row need of their token.
+struct RowCtx {
+    uint32_t off;           // slot of the theta row, 16-byte units
+    int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
+    int o;
+    float w_o;
+    double u, Qp;
+    bool row_on;
+    int ti;                 // token index inside the wave's batch
+};
+
+__device__ __forceinline__ const int32_t* row_counts(const unsigned char* slots, const RowCtx& r) {
+    return reinterpret_cast<const int32_t*>(slots + (size_t)r.off * 16u);
+}
+__device__ __forceinline__ const uint16_t* row_topics(const unsigned char* slots, const RowCtx& r) {
+    return reinterpret_cast<const uint16_t*>(row_counts(slots, r) + ((r.nnz + 3) & ~3));
+}
+
+// Four consecutive entries of a row as they come from memory.
+struct QuadRaw {
+    int4 c;                 // counts
+    uint2 t;                // topics, two per dword
+};
+
+__device__ __forceinline__ QuadRaw quad_load(const unsigned char* slots, const RowCtx& r, int e,
+                                             bool on, int K) {
+    QuadRaw q;
+    q.c = make_int4(0, 0, 0, 0);
+    q.t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
+    if (on) {
+        q.c = *reinterpret_cast<const int4*>(row_counts(slots, r) + e);
+        q.t = *reinterpret_cast<const uint2*>(row_topics(slots, r) + e);
+    }
+    return q;
+}
+
+// p1 = (count - [k = o]) * p*'(k), Eq. 6, accumulated onto `base`:
+// s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
 struct Quad {
     int k[4];
     double s[4];
 };
 
-__device__ __forceinline__ Quad row_quad(const int32_t* cnt, const uint16_t* top, int e, bool on,
-                                         int K, int o, float w_o, const float* pstar, double base) {
-    int4 c = make_int4(0, 0, 0, 0);
-    uint2 t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
-    if (on) {
-        c = *reinterpret_cast<const int4*>(cnt + e);
-        t = *reinterpret_cast<const uint2*>(top + e);
-    }
+__device__ __forceinline__ Quad quad_sums(const QuadRaw& raw, int o, float w_o, const float* pstar,
+                                          double base) {
     Quad q;
-    q.k[0] = (int)(t.x & 0xffffu); q.k[1] = (int)(t.x >> 16);
-    q.k[2] = (int)(t.y & 0xffffu); q.k[3] = (int)(t.y >> 16);
-    const int cc[4] = {c.x, c.y, c.z, c.w};
+    q.k[0] = (int)(raw.t.x & 0xffffu); q.k[1] = (int)(raw.t.x >> 16);
+    q.k[2] = (int)(raw.t.y & 0xffffu); q.k[3] = (int)(raw.t.y >> 16);
+    const int cc[4] = {raw.c.x, raw.c.y, raw.c.z, raw.c.w};
     double acc = base;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -138,18 +171,6 @@ __device__ __forceinline__ Quad row_quad(const int32_t* cnt, const uint16_t* top
     }
     return q;
 }
-
-// What the 16 lanes of a row need of their token, and where the result goes.
-struct RowCtx {
-    const int32_t* cnt;     // the theta row: counts, then topics
-    const uint16_t* top;
-    int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
-    int o;
-    float w_o;
-    double u, Qp;
-    bool row_on;
-    int ti;                 // token index inside the wave's batch
-};
 
 // Row total S (Eq. 7), the draw x = u (S + Q'), and whether this lane's entries hold it.
 struct RowDraw {
@@ -178,17 +199,16 @@ __device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int
     }
 }
 
-// Rows of at most 64 kQuads entries: every lane keeps its prefix sums in registers.
+// Rows of at most 64 kQuads entries, already loaded: every lane keeps its prefix sums in
+// registers.
 template <int kQuads>
-__device__ __forceinline__ void row_pass_kept(const RowCtx& r, int K, const float* pstar, int sl,
-                                              int lane, int* my_res, double* my_y) {
+__device__ __forceinline__ void row_pass_kept(const RowCtx& r, const QuadRaw* raw, const float* pstar,
+                                              int sl, int lane, int* my_res, double* my_y) {
     Quad q[kQuads];
-    const int e0 = sl * 4 * r.n4;
     double acc = 0.0;
 #pragma unroll
     for (int c = 0; c < kQuads; ++c) {
-        const int e = e0 + 4 * c;
-        q[c] = row_quad(r.cnt, r.top, e, c < r.n4 && e < r.nnz, K, r.o, r.w_o, pstar, acc);
+        q[c] = quad_sums(raw[c], r.o, r.w_o, pstar, acc);
         acc = q[c].s[3];
     }
     const RowDraw d = row_draw(acc, r, lane);
@@ -211,13 +231,14 @@ __device__ __forceinline__ void row_pass_kept(const RowCtx& r, int K, const floa
 }
 
 // Longer rows: one walk for the sums, a second one over the hit lane's entries.
-__device__ __forceinline__ void row_pass_long(const RowCtx& r, int n4max, int K, const float* pstar,
-                                              int sl, int lane, int* my_res, double* my_y) {
+__device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int n4max,
+                                              int K, const float* pstar, int sl, int lane,
+                                              int* my_res, double* my_y) {
     const int e0 = sl * 4 * r.n4;
     double acc = 0.0;
     for (int c = 0; c < n4max; ++c) {
         const int e = e0 + 4 * c;
-        const Quad q = row_quad(r.cnt, r.top, e, c < r.n4 && e < r.nnz, K, r.o, r.w_o, pstar, acc);
+        const Quad q = quad_sums(quad_load(slots, r, e, c < r.n4 && e < r.nnz, K), r.o, r.w_o, pstar, acc);
         acc = q.s[3];
     }
     const RowDraw d = row_draw(acc, r, lane);
@@ -228,8 +249,8 @@ __device__ __forceinline__ void row_pass_long(const RowCtx& r, int n4max, int K,
         acc = 0.0;
         for (int c = 0; c < n4max; ++c) {
             const int e = e0 + 4 * c;
-            const Quad q = row_quad(r.cnt, r.top, e, d.hit && c < r.n4 && e < r.nnz, K, r.o, r.w_o,
-                                    pstar, acc);
+            const Quad q = quad_sums(quad_load(slots, r, e, d.hit && c < r.n4 && e < r.nnz, K), r.o,
+                                     r.w_o, pstar, acc);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double before = (j == 0) ? acc : q.s[j - 1];
@@ -315,24 +336,51 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- one token per row of 16 lanes, four tokens per pass
+        // ---- one token per row of 16 lanes, four tokens per pass; the rows of pass p+1 are
+        // requested from memory before pass p is worked on
         const int n_here = min(kWave, tl.count - b * kWave);
-        for (int p = 0; p * kRowsPerWave < n_here; ++p) {
+        const int n_pass = (n_here + kRowsPerWave - 1) / kRowsPerWave;
+        auto row_ctx = [&](int p) {
             RowCtx r;
             r.ti = p * kRowsPerWave + row;
             r.row_on = r.ti < n_here;
             const TokenRec rec = my_rec[r.row_on ? r.ti : 0];
+            r.off = rec.off;
             r.nnz = r.row_on ? rec.nnz : 0;
             r.n4 = (r.nnz + 4 * kRowLanes - 1) / (4 * kRowLanes);
             r.o = rec.o; r.w_o = rec.w_o; r.u = rec.u; r.Qp = rec.Qp;
-            r.cnt = reinterpret_cast<const int32_t*>(a.slots + (size_t)rec.off * 16u);
-            r.top = reinterpret_cast<const uint16_t*>(r.cnt + ((r.nnz + 3) & ~3));
-            const int n4max = max(max(read_lane(r.n4, 0), read_lane(r.n4, 16)),
-                                  max(read_lane(r.n4, 32), read_lane(r.n4, 48)));
-            if (n4max <= 1)      row_pass_kept<1>(r, K, pstar, sl, lane, my_res, my_y);
-            else if (n4max <= 2) row_pass_kept<2>(r, K, pstar, sl, lane, my_res, my_y);
-            else if (n4max <= 4) row_pass_kept<4>(r, K, pstar, sl, lane, my_res, my_y);
-            else                 row_pass_long(r, n4max, K, pstar, sl, lane, my_res, my_y);
+            return r;
+        };
+        auto longest = [&](const RowCtx& r) {          // quads per lane of the pass's longest row
+            return max(max(read_lane(r.n4, 0), read_lane(r.n4, 16)),
+                       max(read_lane(r.n4, 32), read_lane(r.n4, 48)));
+        };
+        auto request = [&](const RowCtx& r, int n4max, QuadRaw* raw) {
+            const bool kept = n4max <= kAheadQuads;    // longer rows are loaded by their own walk
+#pragma unroll
+            for (int c = 0; c < kAheadQuads; ++c) {
+                const int e = sl * 4 * r.n4 + 4 * c;
+                raw[c] = quad_load(a.slots, r, e, kept && c < r.n4 && e < r.nnz, K);
+            }
+        };
+        RowCtx r_next = row_ctx(0);
+        int n4max_next = longest(r_next);
+        QuadRaw raw_next[kAheadQuads];
+        request(r_next, n4max_next, raw_next);
+        for (int p = 0; p < n_pass; ++p) {
+            const RowCtx r = r_next;
+            const int n4max = n4max_next;
+            QuadRaw raw[kAheadQuads];
+#pragma unroll
+            for (int c = 0; c < kAheadQuads; ++c) raw[c] = raw_next[c];
+            if (p + 1 < n_pass) {
+                r_next = row_ctx(p + 1);
+                n4max_next = longest(r_next);
+                request(r_next, n4max_next, raw_next);
+            }
+            if (n4max <= 1)      row_pass_kept<1>(r, raw, pstar, sl, lane, my_res, my_y);
+            else if (n4max <= 2) row_pass_kept<2>(r, raw, pstar, sl, lane, my_res, my_y);
+            else                 row_pass_long(a.slots, r, n4max, K, pstar, sl, lane, my_res, my_y);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
