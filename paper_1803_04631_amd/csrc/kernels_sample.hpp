@@ -12,14 +12,16 @@
 //     p*(o), and the search in the dense bucket p2 (binary search over the group prefixes,
 //     then at most 16 steps);
 //   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
-//     by 16 lanes per token (one DPP row), four tokens per wave at a time: every lane owns
-//     a contiguous run of entries, loaded four at a time as one 16-byte and one 8-byte
-//     load, accumulates them in fp64, and a 4-step in-row DPP scan gives the prefix over
-//     lanes.  The lane whose range holds the draw finds "the smallest k whose prefix exceeds
-//     it" (Section 6.1.1) among its own entries.  Token parameters and results travel
-//     between the per-lane and per-row phases through small per-wave LDS records;
+//     by a GROUP of 16, 32 or 64 lanes per token (one, two or four DPP rows), chosen per pass
+//     from the row lengths so that a lane owns at most eight entries: every lane owns a
+//     contiguous run of entries, loaded four at a time as one 16-byte and one 8-byte load,
+//     accumulates them in fp64 in registers, and a DPP scan over the group gives the prefix
+//     over lanes.  The lane whose range holds the draw finds "the smallest k whose prefix
+//     exceeds it" (Section 6.1.1) among its own entries.  Rows of more than 512 entries are
+//     walked twice by a whole wave.  Token parameters and results travel between the
+//     per-lane and per-group phases through small per-wave LDS records;
 //   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
-//     loads of the next four rows are issued before the current four are worked on.
+//     loads of the next pass are issued before the current pass is worked on.
 #pragma once
 #include "device_util.hpp"
 
@@ -51,11 +53,9 @@ struct SampleArgs {
 };
 
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
-constexpr int kRowLanes = 16;   // lanes that walk one token's theta row (one DPP row)
-constexpr int kRowsPerWave = kWave / kRowLanes;
-constexpr int kAheadQuads = 2;  // quads per lane whose loads are issued one pass ahead
+constexpr int kKeptQuads = 2;   // quads (of four entries) a lane keeps in registers at most
 
-struct __align__(16) TokenRec { // per-lane phase -> per-row phase, 32 bytes
+struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
     uint32_t off;               // slot offset of the token's theta row, 16-byte units
     int32_t nnz;
     int32_t o;                  // current topic
@@ -95,24 +95,37 @@ __device__ __forceinline__ int dense_bucket_search(const float* pstar, const dou
     return found;
 }
 
-// Move within each row of 16 lanes; lanes without a source read 0.
+// DPP move of a double with full row and bank masks; lanes without a source read 0.
 template <int kCtrl>
-__device__ __forceinline__ double row_move0(double v) {
+__device__ __forceinline__ double dpp_move_all0(double v) {
     const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, 0xf, 0xf, true);
     const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, 0xf, 0xf, true);
     return __hiloint2double(hi, lo);
 }
 
-// Inclusive prefix sum inside each row of 16 lanes.  Every lane must be active.
-__device__ __forceinline__ double row_inclusive_sum(double v) {
-    v += row_move0<0x111>(v);   // row_shr:1
-    v += row_move0<0x112>(v);   // row_shr:2
-    v += row_move0<0x114>(v);   // row_shr:4
-    v += row_move0<0x118>(v);   // row_shr:8
+// Inclusive prefix sum inside each group of kLanes (16, 32 or 64) lanes.  Every lane must be
+// active.  Four shifts inside each row of 16 lanes; for wider groups lane 15 of the even
+// rows is added to the odd rows, and for the whole wave lane 31 to rows 2 and 3.
+template <int kLanes>
+__device__ __forceinline__ double group_inclusive_sum(double v) {
+    v += dpp_move_all0<0x111>(v);   // row_shr:1
+    v += dpp_move_all0<0x112>(v);   // row_shr:2
+    v += dpp_move_all0<0x114>(v);   // row_shr:4
+    v += dpp_move_all0<0x118>(v);   // row_shr:8
+    if (kLanes >= 32) v += dpp_move0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    if (kLanes >= 64) v += dpp_move0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
-// What the 16 lanes of a row need of their token.
+// Value of the lane before this one inside the group, 0 for the group's first lane.
+template <int kLanes>
+__device__ __forceinline__ double group_previous(double incl, int sl) {
+    if (kLanes == 16) return dpp_move_all0<0x111>(incl);          // row_shr:1
+    const double up = dpp_move_all0<0x138>(incl);                  // wave_shr:1
+    return sl == 0 ? 0.0 : up;
+}
+
+// What the lanes of a group need of their token.
 struct RowCtx {
     uint32_t off;           // slot of the theta row, 16-byte units
     int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
@@ -121,6 +134,7 @@ struct RowCtx {
     double u, Qp;
     bool row_on;
     int ti;                 // token index inside the wave's batch
+    int sl;                 // lane index inside the group
 };
 
 __device__ __forceinline__ const int32_t* row_counts(const unsigned char* slots, const RowCtx& r) {
@@ -150,23 +164,28 @@ __device__ __forceinline__ QuadRaw quad_load(const unsigned char* slots, const R
 
 // p1 = (count - [k = o]) * p*'(k), Eq. 6, accumulated onto `base`:
 // s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
-struct Quad {
-    int k[4];
+struct QuadSums {
     double s[4];
 };
 
-__device__ __forceinline__ Quad quad_sums(const QuadRaw& raw, int o, float w_o, const float* pstar,
-                                          double base) {
-    Quad q;
-    q.k[0] = (int)(raw.t.x & 0xffffu); q.k[1] = (int)(raw.t.x >> 16);
-    q.k[2] = (int)(raw.t.y & 0xffffu); q.k[3] = (int)(raw.t.y >> 16);
+__device__ __forceinline__ int quad_topic(const uint2& t, int j) {
+    return j == 0 ? (int)(t.x & 0xffffu) : j == 1 ? (int)(t.x >> 16)
+         : j == 2 ? (int)(t.y & 0xffffu) : (int)(t.y >> 16);
+}
+
+__device__ __forceinline__ QuadSums quad_sums(const QuadRaw& raw, int o, float w_o,
+                                              const float* pstar, double base) {
+    QuadSums q;
     const int cc[4] = {raw.c.x, raw.c.y, raw.c.z, raw.c.w};
+    int k[4];
+    float w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { k[j] = quad_topic(raw.t, j); w[j] = pstar[k[j]]; }
     double acc = base;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const bool own = q.k[j] == o;
-        const float w = own ? w_o : pstar[q.k[j]];
-        acc = fma((double)(cc[j] - (own ? 1 : 0)), (double)w, acc);
+        const bool own = k[j] == o;
+        acc = fma((double)(cc[j] - (own ? 1 : 0)), (double)(own ? w_o : w[j]), acc);
         q.s[j] = acc;
     }
     return q;
@@ -174,15 +193,16 @@ __device__ __forceinline__ Quad quad_sums(const QuadRaw& raw, int o, float w_o, 
 
 // Row total S (Eq. 7), the draw x = u (S + Q'), and whether this lane's entries hold it.
 struct RowDraw {
-    double S, x, y;         // y = x - (sum of the lanes before this one)
+    double S, x, y;         // y = x - (sum of the group's lanes before this one)
     bool sparse, hit;
 };
 
+template <int kLanes>
 __device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, int lane) {
     RowDraw d;
-    const double incl = row_inclusive_sum(lane_sum);
-    const double excl = row_move0<0x111>(incl);
-    d.S = __shfl(incl, lane | (kRowLanes - 1), kWave);
+    const double incl = group_inclusive_sum<kLanes>(lane_sum);
+    const double excl = group_previous<kLanes>(incl, r.sl);
+    d.S = __shfl(incl, lane | (kLanes - 1), kWave);
     d.x = r.u * (d.S + r.Qp);
     d.sparse = d.x < d.S;
     d.hit = d.sparse && (incl > d.x) && !(excl > d.x);
@@ -190,78 +210,86 @@ __device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, in
     return d;
 }
 
-__device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int k_sel, int sl,
+__device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int k_sel,
                                           int* my_res, double* my_y) {
     if (d.hit) my_res[r.ti] = k_sel;
-    if (r.row_on && !d.sparse && sl == 0) {
+    if (r.row_on && !d.sparse && r.sl == 0) {
         my_res[r.ti] = -1;                  // the draw falls into the dense bucket p2
         my_y[r.ti] = d.x - d.S;
     }
 }
 
-// Rows of at most 64 kQuads entries, already loaded: every lane keeps its prefix sums in
-// registers.
-template <int kQuads>
+// Rows whose lanes own at most kQuads quads, already loaded: every lane keeps its prefix
+// sums in registers, and the topics packed as loaded.
+template <int kLanes, int kQuads>
 __device__ __forceinline__ void row_pass_kept(const RowCtx& r, const QuadRaw* raw, const float* pstar,
-                                              int sl, int lane, int* my_res, double* my_y) {
-    Quad q[kQuads];
+                                              int lane, int* my_res, double* my_y) {
+    QuadSums q[kQuads];
+    uint2 t[kQuads];
     double acc = 0.0;
 #pragma unroll
     for (int c = 0; c < kQuads; ++c) {
         q[c] = quad_sums(raw[c], r.o, r.w_o, pstar, acc);
+        t[c] = raw[c].t;
         acc = q[c].s[3];
     }
-    const RowDraw d = row_draw(acc, r, lane);
+    const RowDraw d = row_draw<kLanes>(acc, r, lane);
     // smallest entry whose prefix exceeds y (the prefixes never decrease)
-    int k_sel = q[kQuads - 1].k[3];
+    int i_sel = 4 * kQuads - 1;
 #pragma unroll
     for (int i = 4 * kQuads - 2; i >= 0; --i)
-        if (q[i / 4].s[i % 4] > d.y) k_sel = q[i / 4].k[i % 4];
+        if (q[i / 4].s[i % 4] > d.y) i_sel = i;
     if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no prefix above the draw:
         if (d.hit && !(acc > d.y)) {                 // take the lane's last entry with weight
             double before = 0.0;
 #pragma unroll
             for (int i = 0; i < 4 * kQuads; ++i) {
-                if (q[i / 4].s[i % 4] > before) k_sel = q[i / 4].k[i % 4];
+                if (q[i / 4].s[i % 4] > before) i_sel = i;
                 before = q[i / 4].s[i % 4];
             }
         }
     }
-    row_store(r, d, k_sel, sl, my_res, my_y);
+    uint32_t pair = t[0].x;                          // the two topics that hold entry i_sel
+#pragma unroll
+    for (int h = 1; h < 2 * kQuads; ++h)
+        if ((i_sel >> 1) == h) pair = (h & 1) ? t[h / 2].y : t[h / 2].x;
+    const int k_sel = (int)((i_sel & 1) ? (pair >> 16) : (pair & 0xffffu));
+    row_store(r, d, k_sel, my_res, my_y);
 }
 
-// Longer rows: one walk for the sums, a second one over the hit lane's entries.
-__device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int n4max,
-                                              int K, const float* pstar, int sl, int lane,
-                                              int* my_res, double* my_y) {
-    const int e0 = sl * 4 * r.n4;
+// Rows of more than 512 entries, one per wave: one walk for the sums, a second one over the
+// hit lane's entries.
+__device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int K,
+                                              const float* pstar, int lane, int* my_res,
+                                              double* my_y) {
+    const int e0 = r.sl * 4 * r.n4;
     double acc = 0.0;
-    for (int c = 0; c < n4max; ++c) {
+    for (int c = 0; c < r.n4; ++c) {
         const int e = e0 + 4 * c;
-        const Quad q = quad_sums(quad_load(slots, r, e, c < r.n4 && e < r.nnz, K), r.o, r.w_o, pstar, acc);
+        const QuadSums q = quad_sums(quad_load(slots, r, e, e < r.nnz, K), r.o, r.w_o, pstar, acc);
         acc = q.s[3];
     }
-    const RowDraw d = row_draw(acc, r, lane);
+    const RowDraw d = row_draw<kWave>(acc, r, lane);
     int k_sel = 0;
     if (__ballot(d.hit) != 0) {
         bool ok = false;
         int last_k = 0;
         acc = 0.0;
-        for (int c = 0; c < n4max; ++c) {
+        for (int c = 0; c < r.n4; ++c) {
             const int e = e0 + 4 * c;
-            const Quad q = quad_sums(quad_load(slots, r, e, d.hit && c < r.n4 && e < r.nnz, K), r.o,
-                                     r.w_o, pstar, acc);
+            const QuadRaw raw = quad_load(slots, r, e, d.hit && e < r.nnz, K);
+            const QuadSums q = quad_sums(raw, r.o, r.w_o, pstar, acc);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double before = (j == 0) ? acc : q.s[j - 1];
-                if (!ok && q.s[j] > d.y) { k_sel = q.k[j]; ok = true; }
-                if (q.s[j] > before) last_k = q.k[j];
+                if (!ok && q.s[j] > d.y) { k_sel = quad_topic(raw.t, j); ok = true; }
+                if (q.s[j] > before) last_k = quad_topic(raw.t, j);
             }
             acc = q.s[3];
         }
         if (!ok) k_sel = last_k;
     }
-    row_store(r, d, k_sel, sl, my_res, my_y);
+    row_store(r, d, k_sel, my_res, my_y);
 }
 
 template <int kWaves>
@@ -307,7 +335,6 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     __syncthreads();
     const double W = cp[ng - 1];           // sum_k p*(k);  Q = alpha W (Eq. 7)
 
-    const int sl = lane & (kRowLanes - 1), row = lane / kRowLanes;
     const int n_batches = (tl.count + kWave - 1) / kWave;
     for (int b = wave; b < n_batches; b += kWaves) {
         // ---- one token per lane: token, uniform, own-count correction
@@ -336,51 +363,78 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- one token per row of 16 lanes, four tokens per pass; the rows of pass p+1 are
-        // requested from memory before pass p is worked on
+        // ---- one token per group of 16 / 32 / 64 lanes.  A pass takes the next 4, 2 or 1
+        // tokens, whichever lets every lane own at most kKeptQuads quads; the rows of the
+        // following pass are requested from memory before this one is worked on.
         const int n_here = min(kWave, tl.count - b * kWave);
-        const int n_pass = (n_here + kRowsPerWave - 1) / kRowsPerWave;
-        auto row_ctx = [&](int p) {
+        // which tokens of the batch have rows beyond 64 / 128 / 256 / 512 entries (lanes past
+        // the batch's end hold nnz = 0): the shape of every pass follows from these masks
+        const uint64_t over64 = __ballot(mine.nnz > 16 * 4), over128 = __ballot(mine.nnz > 16 * 8);
+        const uint64_t over256 = __ballot(mine.nnz > 32 * 8), over512 = __ballot(mine.nnz > 64 * 8);
+        static_assert(kKeptQuads == 2, "the pass shapes assume two kept quads per lane");
+        auto lanes_for = [&](int t0) {               // group width of the pass starting at t0
+            return ((over128 >> t0) & 0xfull) == 0 ? 16 : ((over256 >> t0) & 0x3ull) == 0 ? 32 : 64;
+        };
+        // where a pass's rows are, and the loads of the quads its lanes keep (lanes = 16, 32, 64)
+        auto request = [&](int t0, int lanes, uint32_t& off, int& nnz, QuadRaw* raw) {
+            const int shift = lanes == 16 ? 4 : lanes == 32 ? 5 : 6;
+            const int ti = t0 + (lane >> shift);
+            const bool on = ti < n_here;
+            const uint2 where = *reinterpret_cast<const uint2*>(&my_rec[on ? ti : 0]);
+            off = where.x;
+            nnz = on ? (int)where.y : 0;
             RowCtx r;
-            r.ti = p * kRowsPerWave + row;
+            r.off = off; r.nnz = nnz;
+            const int n4 = (nnz + 4 * lanes - 1) >> (shift + 2);
+            const bool kept = n4 <= kKeptQuads;        // longer rows are loaded by their own walk
+#pragma unroll
+            for (int c = 0; c < kKeptQuads; ++c) {
+                const int e = (lane & (lanes - 1)) * 4 * n4 + 4 * c;
+                raw[c] = quad_load(a.slots, r, e, kept && c < n4 && e < nnz, K);
+            }
+        };
+        auto row_ctx = [&](int t0, int lanes, uint32_t off, int nnz) {
+            const int shift = lanes == 16 ? 4 : lanes == 32 ? 5 : 6;
+            RowCtx r;
+            r.sl = lane & (lanes - 1);
+            r.ti = t0 + (lane >> shift);
             r.row_on = r.ti < n_here;
-            const TokenRec rec = my_rec[r.row_on ? r.ti : 0];
-            r.off = rec.off;
-            r.nnz = r.row_on ? rec.nnz : 0;
-            r.n4 = (r.nnz + 4 * kRowLanes - 1) / (4 * kRowLanes);
-            r.o = rec.o; r.w_o = rec.w_o; r.u = rec.u; r.Qp = rec.Qp;
+            r.off = off;
+            r.nnz = nnz;
+            r.n4 = (nnz + 4 * lanes - 1) >> (shift + 2);
+            const TokenRec* rec = &my_rec[r.row_on ? r.ti : 0];
+            const int2 ow = *reinterpret_cast<const int2*>(&rec->o);
+            const double2 uq = *reinterpret_cast<const double2*>(&rec->u);
+            r.o = ow.x; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
             return r;
         };
-        auto longest = [&](const RowCtx& r) {          // quads per lane of the pass's longest row
-            return max(max(read_lane(r.n4, 0), read_lane(r.n4, 16)),
-                       max(read_lane(r.n4, 32), read_lane(r.n4, 48)));
-        };
-        auto request = [&](const RowCtx& r, int n4max, QuadRaw* raw) {
-            const bool kept = n4max <= kAheadQuads;    // longer rows are loaded by their own walk
+        int t_next = 0, lanes_next = lanes_for(0), nnz_next;
+        uint32_t off_next;
+        QuadRaw raw_next[kKeptQuads];
+        request(0, lanes_next, off_next, nnz_next, raw_next);
+        while (t_next < n_here) {
+            const int lanes = lanes_next, t_cur = t_next;
+            const RowCtx r = row_ctx(t_cur, lanes, off_next, nnz_next);
+            QuadRaw raw[kKeptQuads];
 #pragma unroll
-            for (int c = 0; c < kAheadQuads; ++c) {
-                const int e = sl * 4 * r.n4 + 4 * c;
-                raw[c] = quad_load(a.slots, r, e, kept && c < r.n4 && e < r.nnz, K);
+            for (int c = 0; c < kKeptQuads; ++c) raw[c] = raw_next[c];
+            t_next += kWave / lanes;
+            if (t_next < n_here) {
+                lanes_next = lanes_for(t_next);
+                request(t_next, lanes_next, off_next, nnz_next, raw_next);
             }
-        };
-        RowCtx r_next = row_ctx(0);
-        int n4max_next = longest(r_next);
-        QuadRaw raw_next[kAheadQuads];
-        request(r_next, n4max_next, raw_next);
-        for (int p = 0; p < n_pass; ++p) {
-            const RowCtx r = r_next;
-            const int n4max = n4max_next;
-            QuadRaw raw[kAheadQuads];
-#pragma unroll
-            for (int c = 0; c < kAheadQuads; ++c) raw[c] = raw_next[c];
-            if (p + 1 < n_pass) {
-                r_next = row_ctx(p + 1);
-                n4max_next = longest(r_next);
-                request(r_next, n4max_next, raw_next);
+            if (lanes == 16) {
+                if (((over64 >> t_cur) & 0xfull) == 0)
+                    row_pass_kept<16, 1>(r, raw, pstar, lane, my_res, my_y);
+                else
+                    row_pass_kept<16, 2>(r, raw, pstar, lane, my_res, my_y);
+            } else if (lanes == 32) {
+                row_pass_kept<32, 2>(r, raw, pstar, lane, my_res, my_y);
+            } else if (((over512 >> t_cur) & 1ull) == 0) {
+                row_pass_kept<64, 2>(r, raw, pstar, lane, my_res, my_y);
+            } else {
+                row_pass_long(a.slots, r, K, pstar, lane, my_res, my_y);
             }
-            if (n4max <= 1)      row_pass_kept<1>(r, raw, pstar, sl, lane, my_res, my_y);
-            else if (n4max <= 2) row_pass_kept<2>(r, raw, pstar, sl, lane, my_res, my_y);
-            else                 row_pass_long(a.slots, r, n4max, K, pstar, sl, lane, my_res, my_y);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();

@@ -39,7 +39,8 @@ int fail(int code, const std::string& msg) {
 
 constexpr size_t kAlign = 256;        // workspace sub-buffer alignment
 constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
-constexpr int kSampleWaves = 4;
+// waves per sampling workgroup: more of them share one staged p* column when K is large
+int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 16; }
 constexpr int kMaxTimedIters = 1024;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -273,7 +274,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     HIP_TRY(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
     // one zero entry of p* past the last topic: padding entries of theta rows point at it
     const int32_t Kpad = (K + mlda::kGroup) / mlda::kGroup * mlda::kGroup;
-    const size_t sample_lds = mlda::sample_lds_bytes(Kpad, kSampleWaves);
+    const size_t sample_lds = mlda::sample_lds_bytes(Kpad, sample_waves_for(K));
     if (sample_lds > (size_t)lds_limit)
         return fail(MLDA_ENOTSUP, "K = " + std::to_string(K) + " needs " + std::to_string(sample_lds) +
                                       " bytes of LDS per workgroup, the device allows " +
@@ -468,7 +469,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         e = hipGetLastError();
     }
     if (e == hipSuccess && sample_lds > 48 * 1024)
-        e = hipFuncSetAttribute((const void*)mlda::sample_kernel<kSampleWaves>,
+        e = hipFuncSetAttribute(sample_waves_for(K) == 4 ? (const void*)mlda::sample_kernel<4>
+                                                         : (const void*)mlda::sample_kernel<16>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sample_lds);
     if (e == hipSuccess && (size_t)K * 4 > 48 * 1024) {
         e = hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
@@ -561,8 +563,12 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
             a.beta_V = c->beta * (double)c->V;
             a.seed = c->seed;
             a.iter = (uint32_t)(c->iter + 1);
-            hipLaunchKernelGGL(mlda::sample_kernel<kSampleWaves>, dim3((unsigned)c->n_tiles),
-                               dim3(kSampleWaves * mlda::kWave), c->sample_lds, c->stream, a);
+            if (sample_waves_for(c->K) == 4)
+                hipLaunchKernelGGL(mlda::sample_kernel<4>, dim3((unsigned)c->n_tiles),
+                                   dim3(4 * mlda::kWave), c->sample_lds, c->stream, a);
+            else
+                hipLaunchKernelGGL(mlda::sample_kernel<16>, dim3((unsigned)c->n_tiles),
+                                   dim3(16 * mlda::kWave), c->sample_lds, c->stream, a);
             rc = launch_check("sample_kernel");
             if (rc != MLDA_OK) return rc;
         }
