@@ -298,14 +298,18 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     const int K = a.K, Kpad = a.Kpad, ng = Kpad / kGroup;
     float* pstar = reinterpret_cast<float*>(lds);
     double* cp = reinterpret_cast<double*>(lds + (size_t)Kpad * 4);
-    const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = (int)threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);      // wave-uniform, in an SGPR
     unsigned char* wave_base = lds + (size_t)Kpad * 4 + (size_t)((ng + 1) & ~1) * 8;
     double* my_y = reinterpret_cast<double*>(wave_base) + wave * kWave;
     TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base + (size_t)kWaves * kWave * 8) + wave * kWave;
     int* my_res = reinterpret_cast<int*>(wave_base + (size_t)kWaves * kWave * (8 + sizeof(TokenRec))) +
                   wave * kWave;
 
-    const Tile tl = a.tiles[blockIdx.x];
+    Tile tl = a.tiles[blockIdx.x];         // the same for every lane: keep it in SGPRs
+    tl.word = __builtin_amdgcn_readfirstlane(tl.word);
+    tl.begin = __builtin_amdgcn_readfirstlane(tl.begin);
+    tl.count = __builtin_amdgcn_readfirstlane(tl.count);
     const int32_t* phi_v = a.n_wk + (size_t)tl.word * (size_t)K;
 
     // ---- stage p*(k) = (phi_kv + beta)/(n_k + beta V) as fp32 (Eq. 8)
@@ -410,31 +414,34 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         };
         int t_next = 0, lanes_next = lanes_for(0), nnz_next;
         uint32_t off_next;
-        QuadRaw raw_next[kKeptQuads];
-        request(0, lanes_next, off_next, nnz_next, raw_next);
-        while (t_next < n_here) {
+        // one pass: `mine_raw` holds its rows, already requested; the following pass's rows
+        // go to `next_raw`.  The two buffers swap roles from pass to pass.
+        auto pass = [&](QuadRaw* mine_raw, QuadRaw* next_raw) {
             const int lanes = lanes_next, t_cur = t_next;
             const RowCtx r = row_ctx(t_cur, lanes, off_next, nnz_next);
-            QuadRaw raw[kKeptQuads];
-#pragma unroll
-            for (int c = 0; c < kKeptQuads; ++c) raw[c] = raw_next[c];
-            t_next += kWave / lanes;
+            t_next += lanes == 16 ? 4 : lanes == 32 ? 2 : 1;
             if (t_next < n_here) {
                 lanes_next = lanes_for(t_next);
-                request(t_next, lanes_next, off_next, nnz_next, raw_next);
+                request(t_next, lanes_next, off_next, nnz_next, next_raw);
             }
             if (lanes == 16) {
                 if (((over64 >> t_cur) & 0xfull) == 0)
-                    row_pass_kept<16, 1>(r, raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<16, 1>(r, mine_raw, pstar, lane, my_res, my_y);
                 else
-                    row_pass_kept<16, 2>(r, raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<16, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else if (lanes == 32) {
-                row_pass_kept<32, 2>(r, raw, pstar, lane, my_res, my_y);
+                row_pass_kept<32, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else if (((over512 >> t_cur) & 1ull) == 0) {
-                row_pass_kept<64, 2>(r, raw, pstar, lane, my_res, my_y);
+                row_pass_kept<64, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else {
                 row_pass_long(a.slots, r, K, pstar, lane, my_res, my_y);
             }
+        };
+        QuadRaw raw_a[kKeptQuads], raw_b[kKeptQuads];
+        request(0, lanes_next, off_next, nnz_next, raw_a);
+        while (t_next < n_here) {
+            pass(raw_a, raw_b);
+            if (t_next < n_here) pass(raw_b, raw_a);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
