@@ -15,7 +15,6 @@ HIPCC_FLAGS = [
     # no packed-fp32 instruction forms
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
-    *os.environ.get("MLDA_EXTRA_HIPCC_FLAGS", "").split(),
 ]
 
 
