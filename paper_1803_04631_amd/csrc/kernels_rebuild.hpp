@@ -139,10 +139,11 @@ __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const 
 // together gather from neighbouring lines of z.  The walk is a chain of dependent loads
 // (record -> map -> z), so it is software-pipelined: while the current document's topics are
 // gathered, the map entries of the wave's next document and the record of the one after are
-// already on their way.  Row layout: int32 counts[round4(nnz)] then uint16
-// topics[round4(nnz)]; padding entries hold count 0 and topic K.
+// already on their way.  Rows are written in the layout the sampler reads (SplitRows or
+// PackedRows, see kernels_sample.hpp); padding entries hold count 0 and topic K.
 // While the counts pass through registers the kernel also adds up the theta entries' term of
 // the log-likelihood, sum_{d,k} lgG(n_dk + alpha) - lgG(alpha), one partial per workgroup.
+template <bool kPacked>
 __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                                                            const int32_t* doc_map,
                                                            const uint16_t* z, uint2* row_rec,
@@ -187,8 +188,10 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         const int nnz = wave_sum(fresh);
         __syncthreads();
         const int nnz_pad = (nnz + 3) & ~3;
+        // SplitRows: int32 counts then uint16 topics; PackedRows: uint32 count << 18 | topic << 2
         int32_t* cnt = reinterpret_cast<int32_t*>(slots + (size_t)cur.slot * 16u);
         uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
+        uint32_t* ent = reinterpret_cast<uint32_t*>(cnt);
         int filled = 0;
         for (int base = 0; base < K; base += kWave) {
             const int k = base + lane;
@@ -197,8 +200,12 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
             if (m == 0) continue;
             if (c > 0) {
                 const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
-                cnt[at] = c;
-                top[at] = (uint16_t)k;
+                if (kPacked) {
+                    ent[at] = ((uint32_t)c << 18) | ((uint32_t)k << 2);
+                } else {
+                    cnt[at] = c;
+                    top[at] = (uint16_t)k;
+                }
                 hist[k] = 0;
                 if (c < kThetaLgTable) ll += table[c];
             }
@@ -208,7 +215,10 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
             }
             filled += __popcll((unsigned long long)m);
         }
-        if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
+        if (lane < nnz_pad - nnz) {
+            if (kPacked) ent[nnz + lane] = (uint32_t)K << 2;
+            else { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
+        }
         if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;
         visited += (unsigned long long)cur.n * (unsigned long long)nnz;
         __syncthreads();

@@ -41,7 +41,7 @@ struct SampleArgs {
     const uint16_t* z_cur;      // [T] word-major, frozen for the pass
     uint16_t* z_next;           // [T] word-major, written
     const uint2* row_rec;       // [D] {slot offset in 16-byte units, nnz of the theta row}
-    // theta rows: int32 counts[round4(nnz)] then uint16 topics[round4(nnz)]; padding entries
+    // theta rows, in one of the two layouts below (SplitRows / PackedRows); padding entries
     // hold count 0 and topic K
     const unsigned char* slots;
     const int32_t* n_wk;        // [V][K]
@@ -129,7 +129,7 @@ __device__ __forceinline__ double group_previous(double incl, int sl) {
 struct RowCtx {
     uint32_t off;           // slot of the theta row, 16-byte units
     int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
-    int o;
+    int o_key;              // 4 * current topic (a topic's key is its byte offset in p*)
     float w_o;
     double u, Qp;
     bool row_on;
@@ -137,30 +137,76 @@ struct RowCtx {
     int sl;                 // lane index inside the group
 };
 
-__device__ __forceinline__ const int32_t* row_counts(const unsigned char* slots, const RowCtx& r) {
-    return reinterpret_cast<const int32_t*>(slots + (size_t)r.off * 16u);
-}
-__device__ __forceinline__ const uint16_t* row_topics(const unsigned char* slots, const RowCtx& r) {
-    return reinterpret_cast<const uint16_t*>(row_counts(slots, r) + ((r.nnz + 3) & ~3));
-}
-
-// Four consecutive entries of a row as they come from memory.
-struct QuadRaw {
-    int4 c;                 // counts
-    uint2 t;                // topics, two per dword
+// Layout of a theta row inside its slot, 6 bytes per entry: int32 counts[round4(nnz)] then
+// uint16 topics[round4(nnz)].  Always usable.
+struct SplitRows {
+    static constexpr int kEntryBytes = 6;
+    struct Raw {            // four consecutive entries as they come from memory
+        int4 c;             // counts
+        uint2 t;            // topics, two per dword
+    };
+    static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int nnz,
+                                               int e, bool on, int K) {
+        Raw q;
+        q.c = make_int4(0, 0, 0, 0);
+        q.t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
+        if (on) {
+            const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)off * 16u);
+            const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz + 3) & ~3));
+            q.c = *reinterpret_cast<const int4*>(cnt + e);
+            q.t = *reinterpret_cast<const uint2*>(top + e);
+        }
+        return q;
+    }
+    static __device__ __forceinline__ int count(const Raw& q, int j) {
+        return j == 0 ? q.c.x : j == 1 ? q.c.y : j == 2 ? q.c.z : q.c.w;
+    }
+    static __device__ __forceinline__ int key(const Raw& q, int j) {
+        return j == 0 ? (int)((q.t.x & 0xffffu) << 2) : j == 1 ? (int)((q.t.x >> 16) << 2)
+             : j == 2 ? (int)((q.t.y & 0xffffu) << 2) : (int)((q.t.y >> 16) << 2);
+    }
+    // what the search remembers of entry i of a lane's quads, and the topic it stands for
+    static __device__ __forceinline__ uint32_t handle(const Raw*, int i) { return (uint32_t)i; }
+    template <int kQuads>
+    static __device__ __forceinline__ int topic_of(const Raw* raw, uint32_t h) {
+        uint32_t pair = raw[0].t.x;
+#pragma unroll
+        for (int p = 1; p < 2 * kQuads; ++p)
+            if ((h >> 1) == (uint32_t)p) pair = (p & 1) ? raw[p / 2].t.y : raw[p / 2].t.x;
+        return (int)((h & 1u) ? (pair >> 16) : (pair & 0xffffu));
+    }
 };
 
-__device__ __forceinline__ QuadRaw quad_load(const unsigned char* slots, const RowCtx& r, int e,
-                                             bool on, int K) {
-    QuadRaw q;
-    q.c = make_int4(0, 0, 0, 0);
-    q.t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
-    if (on) {
-        q.c = *reinterpret_cast<const int4*>(row_counts(slots, r) + e);
-        q.t = *reinterpret_cast<const uint2*>(row_topics(slots, r) + e);
+// 4 bytes per entry: uint32 entries[round4(nnz)], entry = count << 18 | topic << 2, so that the
+// low 18 bits are the topic's key.  Usable when no document has 16384 tokens or more.
+struct PackedRows {
+    static constexpr int kEntryBytes = 4;
+    static constexpr int kMaxCount = (1 << 14) - 1;
+    struct Raw {
+        uint4 e;
+    };
+    static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int,
+                                               int e, bool on, int K) {
+        Raw q;
+        q.e = make_uint4((uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2);
+        if (on)
+            q.e = *reinterpret_cast<const uint4*>(
+                reinterpret_cast<const uint32_t*>(slots + (size_t)off * 16u) + e);
+        return q;
     }
-    return q;
-}
+    static __device__ __forceinline__ uint32_t entry(const Raw& q, int j) {
+        return j == 0 ? q.e.x : j == 1 ? q.e.y : j == 2 ? q.e.z : q.e.w;
+    }
+    static __device__ __forceinline__ int count(const Raw& q, int j) { return (int)(entry(q, j) >> 18); }
+    static __device__ __forceinline__ int key(const Raw& q, int j) { return (int)(entry(q, j) & 0x3fffcu); }
+    static __device__ __forceinline__ uint32_t handle(const Raw* raw, int i) {
+        return entry(raw[i / 4], i % 4);
+    }
+    template <int kQuads>
+    static __device__ __forceinline__ int topic_of(const Raw*, uint32_t h) {
+        return (int)((h >> 2) & 0xffffu);
+    }
+};
 
 // p1 = (count - [k = o]) * p*'(k), Eq. 6, accumulated onto `base`:
 // s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
@@ -168,24 +214,22 @@ struct QuadSums {
     double s[4];
 };
 
-__device__ __forceinline__ int quad_topic(const uint2& t, int j) {
-    return j == 0 ? (int)(t.x & 0xffffu) : j == 1 ? (int)(t.x >> 16)
-         : j == 2 ? (int)(t.y & 0xffffu) : (int)(t.y >> 16);
-}
-
-__device__ __forceinline__ QuadSums quad_sums(const QuadRaw& raw, int o, float w_o,
+template <class Layout>
+__device__ __forceinline__ QuadSums quad_sums(const typename Layout::Raw& raw, int o_key, float w_o,
                                               const float* pstar, double base) {
     QuadSums q;
-    const int cc[4] = {raw.c.x, raw.c.y, raw.c.z, raw.c.w};
-    int k[4];
+    int key[4];
     float w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { k[j] = quad_topic(raw.t, j); w[j] = pstar[k[j]]; }
+    for (int j = 0; j < 4; ++j) {
+        key[j] = Layout::key(raw, j);
+        w[j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(pstar) + key[j]);
+    }
     double acc = base;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const bool own = k[j] == o;
-        acc = fma((double)(cc[j] - (own ? 1 : 0)), (double)(own ? w_o : w[j]), acc);
+        const bool own = key[j] == o_key;
+        acc = fma((double)(Layout::count(raw, j) - (own ? 1 : 0)), (double)(own ? w_o : w[j]), acc);
         q.s[j] = acc;
     }
     return q;
@@ -220,45 +264,40 @@ __device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int
 }
 
 // Rows whose lanes own at most kQuads quads, already loaded: every lane keeps its prefix
-// sums in registers, and the topics packed as loaded.
-template <int kLanes, int kQuads>
-__device__ __forceinline__ void row_pass_kept(const RowCtx& r, const QuadRaw* raw, const float* pstar,
-                                              int lane, int* my_res, double* my_y) {
+// sums in registers, and the entries as loaded.
+template <class Layout, int kLanes, int kQuads>
+__device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename Layout::Raw* raw,
+                                              const float* pstar, int lane, int* my_res,
+                                              double* my_y) {
     QuadSums q[kQuads];
-    uint2 t[kQuads];
     double acc = 0.0;
 #pragma unroll
     for (int c = 0; c < kQuads; ++c) {
-        q[c] = quad_sums(raw[c], r.o, r.w_o, pstar, acc);
-        t[c] = raw[c].t;
+        q[c] = quad_sums<Layout>(raw[c], r.o_key, r.w_o, pstar, acc);
         acc = q[c].s[3];
     }
     const RowDraw d = row_draw<kLanes>(acc, r, lane);
     // smallest entry whose prefix exceeds y (the prefixes never decrease)
-    int i_sel = 4 * kQuads - 1;
+    uint32_t sel = Layout::handle(raw, 4 * kQuads - 1);
 #pragma unroll
     for (int i = 4 * kQuads - 2; i >= 0; --i)
-        if (q[i / 4].s[i % 4] > d.y) i_sel = i;
+        if (q[i / 4].s[i % 4] > d.y) sel = Layout::handle(raw, i);
     if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no prefix above the draw:
         if (d.hit && !(acc > d.y)) {                 // take the lane's last entry with weight
             double before = 0.0;
 #pragma unroll
             for (int i = 0; i < 4 * kQuads; ++i) {
-                if (q[i / 4].s[i % 4] > before) i_sel = i;
+                if (q[i / 4].s[i % 4] > before) sel = Layout::handle(raw, i);
                 before = q[i / 4].s[i % 4];
             }
         }
     }
-    uint32_t pair = t[0].x;                          // the two topics that hold entry i_sel
-#pragma unroll
-    for (int h = 1; h < 2 * kQuads; ++h)
-        if ((i_sel >> 1) == h) pair = (h & 1) ? t[h / 2].y : t[h / 2].x;
-    const int k_sel = (int)((i_sel & 1) ? (pair >> 16) : (pair & 0xffffu));
-    row_store(r, d, k_sel, my_res, my_y);
+    row_store(r, d, Layout::template topic_of<kQuads>(raw, sel), my_res, my_y);
 }
 
 // Rows of more than 512 entries, one per wave: one walk for the sums, a second one over the
 // hit lane's entries.
+template <class Layout>
 __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int K,
                                               const float* pstar, int lane, int* my_res,
                                               double* my_y) {
@@ -266,7 +305,8 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const 
     double acc = 0.0;
     for (int c = 0; c < r.n4; ++c) {
         const int e = e0 + 4 * c;
-        const QuadSums q = quad_sums(quad_load(slots, r, e, e < r.nnz, K), r.o, r.w_o, pstar, acc);
+        const QuadSums q = quad_sums<Layout>(Layout::load(slots, r.off, r.nnz, e, e < r.nnz, K),
+                                             r.o_key, r.w_o, pstar, acc);
         acc = q.s[3];
     }
     const RowDraw d = row_draw<kWave>(acc, r, lane);
@@ -277,13 +317,13 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const 
         acc = 0.0;
         for (int c = 0; c < r.n4; ++c) {
             const int e = e0 + 4 * c;
-            const QuadRaw raw = quad_load(slots, r, e, d.hit && e < r.nnz, K);
-            const QuadSums q = quad_sums(raw, r.o, r.w_o, pstar, acc);
+            const typename Layout::Raw raw = Layout::load(slots, r.off, r.nnz, e, d.hit && e < r.nnz, K);
+            const QuadSums q = quad_sums<Layout>(raw, r.o_key, r.w_o, pstar, acc);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double before = (j == 0) ? acc : q.s[j - 1];
-                if (!ok && q.s[j] > d.y) { k_sel = quad_topic(raw.t, j); ok = true; }
-                if (q.s[j] > before) last_k = quad_topic(raw.t, j);
+                if (!ok && q.s[j] > d.y) { k_sel = Layout::key(raw, j) >> 2; ok = true; }
+                if (q.s[j] > before) last_k = Layout::key(raw, j) >> 2;
             }
             acc = q.s[3];
         }
@@ -292,7 +332,7 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const 
     row_store(r, d, k_sel, my_res, my_y);
 }
 
-template <int kWaves>
+template <int kWaves, class Layout>
 // Six waves per SIMD (80 VGPRs): the walk hides HBM latency by occupancy as well as by the
 // one-pass-ahead loads; measured faster than five waves with no spills.
 __attribute__((amdgpu_waves_per_eu(6)))
@@ -383,21 +423,20 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             return ((over128 >> t0) & 0xfull) == 0 ? 16 : ((over256 >> t0) & 0x3ull) == 0 ? 32 : 64;
         };
         // where a pass's rows are, and the loads of the quads its lanes keep (lanes = 16, 32, 64)
-        auto request = [&](int t0, int lanes, uint32_t& off, int& nnz, QuadRaw* raw) {
+        using Raw = typename Layout::Raw;
+        auto request = [&](int t0, int lanes, uint32_t& off, int& nnz, Raw* raw) {
             const int shift = lanes == 16 ? 4 : lanes == 32 ? 5 : 6;
             const int ti = t0 + (lane >> shift);
             const bool on = ti < n_here;
             const uint2 where = *reinterpret_cast<const uint2*>(&my_rec[on ? ti : 0]);
             off = where.x;
             nnz = on ? (int)where.y : 0;
-            RowCtx r;
-            r.off = off; r.nnz = nnz;
             const int n4 = (nnz + 4 * lanes - 1) >> (shift + 2);
             const bool kept = n4 <= kKeptQuads;        // longer rows are loaded by their own walk
 #pragma unroll
             for (int c = 0; c < kKeptQuads; ++c) {
                 const int e = (lane & (lanes - 1)) * 4 * n4 + 4 * c;
-                raw[c] = quad_load(a.slots, r, e, kept && c < n4 && e < nnz, K);
+                raw[c] = Layout::load(a.slots, off, nnz, e, kept && c < n4 && e < nnz, K);
             }
         };
         auto row_ctx = [&](int t0, int lanes, uint32_t off, int nnz) {
@@ -412,14 +451,14 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             const TokenRec* rec = &my_rec[r.row_on ? r.ti : 0];
             const int2 ow = *reinterpret_cast<const int2*>(&rec->o);
             const double2 uq = *reinterpret_cast<const double2*>(&rec->u);
-            r.o = ow.x; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
+            r.o_key = ow.x << 2; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
             return r;
         };
         int t_next = 0, lanes_next = lanes_for(0), nnz_next;
         uint32_t off_next;
         // one pass: `mine_raw` holds its rows, already requested; the following pass's rows
         // go to `next_raw`.  The two buffers swap roles from pass to pass.
-        auto pass = [&](QuadRaw* mine_raw, QuadRaw* next_raw) {
+        auto pass = [&](Raw* mine_raw, Raw* next_raw) {
             const int lanes = lanes_next, t_cur = t_next;
             const RowCtx r = row_ctx(t_cur, lanes, off_next, nnz_next);
             t_next += lanes == 16 ? 4 : lanes == 32 ? 2 : 1;
@@ -429,18 +468,18 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             }
             if (lanes == 16) {
                 if (((over64 >> t_cur) & 0xfull) == 0)
-                    row_pass_kept<16, 1>(r, mine_raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<Layout, 16, 1>(r, mine_raw, pstar, lane, my_res, my_y);
                 else
-                    row_pass_kept<16, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<Layout, 16, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else if (lanes == 32) {
-                row_pass_kept<32, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                row_pass_kept<Layout, 32, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else if (((over512 >> t_cur) & 1ull) == 0) {
-                row_pass_kept<64, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                row_pass_kept<Layout, 64, 2>(r, mine_raw, pstar, lane, my_res, my_y);
             } else {
-                row_pass_long(a.slots, r, K, pstar, lane, my_res, my_y);
+                row_pass_long<Layout>(a.slots, r, K, pstar, lane, my_res, my_y);
             }
         };
-        QuadRaw raw_a[kKeptQuads], raw_b[kKeptQuads];
+        Raw raw_a[kKeptQuads], raw_b[kKeptQuads];
         request(0, lanes_next, off_next, nnz_next, raw_a);
         while (t_next < n_here) {
             pass(raw_a, raw_b);

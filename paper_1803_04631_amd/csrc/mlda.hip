@@ -41,6 +41,14 @@ constexpr size_t kAlign = 256;        // workspace sub-buffer alignment
 constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
 // waves per sampling workgroup: more of them share one staged p* column when K is large
 int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 16; }
+
+const void* sample_kernel_for(int32_t K, bool packed) {
+    if (sample_waves_for(K) == 4)
+        return packed ? (const void*)mlda::sample_kernel<4, mlda::PackedRows>
+                      : (const void*)mlda::sample_kernel<4, mlda::SplitRows>;
+    return packed ? (const void*)mlda::sample_kernel<16, mlda::PackedRows>
+                  : (const void*)mlda::sample_kernel<16, mlda::SplitRows>;
+}
 constexpr int kMaxTimedIters = 1024;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -48,8 +56,8 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
 constexpr int kPhiSegment = 16384;    // tokens one workgroup histograms for the phi rebuild
 
-size_t slot_bytes_for(int64_t cap) {   // cap = largest nnz the row can reach
-    return align_up((size_t)(((cap + 3) & ~(int64_t)3) * 6), kSlotAlign);
+size_t slot_bytes_for(int64_t cap, int entry_bytes) {   // cap = largest nnz the row can reach
+    return align_up((size_t)(((cap + 3) & ~(int64_t)3) * entry_bytes), kSlotAlign);
 }
 
 // Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
@@ -123,6 +131,7 @@ struct mlda_ctx {
     int32_t *tok_doc = nullptr, *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
     mlda::DocRec* doc_order = nullptr;  // documents by falling length, as the theta rebuild walks them
     int32_t theta_grid = 0;
+    bool packed = false;                // theta rows as 4-byte entries (no document has 2^14 tokens)
     int32_t *n_wk = nullptr, *n_k = nullptr, *split_words = nullptr;
     uint16_t* z[2] = {nullptr, nullptr};
     int cur = 0;
@@ -180,10 +189,16 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
         const size_t theta_lds = ((hist_bytes + 15) & ~(size_t)15) + (size_t)kThetaLgTable * 8;
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
-        hipLaunchKernelGGL(theta_rows_kernel, dim3((unsigned)c->theta_grid), dim3(kWave), theta_lds,
-                           c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
-                           c->D, c->K, c->alpha, c->lg_table, entries,
-                           c->ll_partial + 2 * kLoglikBlocks);
+        if (c->packed)
+            hipLaunchKernelGGL(theta_rows_kernel<true>, dim3((unsigned)c->theta_grid), dim3(kWave),
+                               theta_lds, c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
+                               c->D, c->K, c->alpha, c->lg_table, entries,
+                               c->ll_partial + 2 * kLoglikBlocks);
+        else
+            hipLaunchKernelGGL(theta_rows_kernel<false>, dim3((unsigned)c->theta_grid), dim3(kWave),
+                               theta_lds, c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
+                               c->D, c->K, c->alpha, c->lg_table, entries,
+                               c->ll_partial + 2 * kLoglikBlocks);
     }
     c->rebuilds += 1;
     if (ev_theta) HIP_TRY(hipEventRecord(*ev_theta, c->stream));
@@ -285,13 +300,17 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     // similar lengths; any order inside a word gives the same result, because the uniforms
     // are keyed by the caller's token index.  Stable counting sort by word over chunks of
     // the length-sorted document sequence.
+    int64_t longest_doc = 0;
+    for (int64_t d = 0; d < D; ++d) longest_doc = std::max(longest_doc, doc_ptr[d + 1] - doc_ptr[d]);
+    // a count never exceeds the document's length: 4-byte theta entries if 14 bits hold it
+    const bool packed = longest_doc <= mlda::PackedRows::kMaxCount;
+    const int entry_bytes = packed ? mlda::PackedRows::kEntryBytes : mlda::SplitRows::kEntryBytes;
     std::vector<int32_t> doc_order;
     std::vector<int64_t> order_tokens;           // tokens before each position of doc_order
     try {
         doc_order.resize((size_t)D);
         order_tokens.resize((size_t)D + 1);
-        int64_t max_len = 0;
-        for (int64_t d = 0; d < D; ++d) max_len = std::max(max_len, doc_ptr[d + 1] - doc_ptr[d]);
+        const int64_t max_len = longest_doc;
         std::vector<int64_t> len_start((size_t)max_len + 2, 0);
         for (int64_t d = 0; d < D; ++d) ++len_start[(size_t)(max_len - (doc_ptr[d + 1] - doc_ptr[d])) + 1];
         for (int64_t l = 0; l <= max_len; ++l) len_start[(size_t)l + 1] += len_start[(size_t)l];
@@ -374,7 +393,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         for (int64_t d = 0; d < D; ++d) {
             const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
             row_rec[d] = make_uint2((uint32_t)(slots_bytes / 16), 0u);
-            slots_bytes += slot_bytes_for(cap);
+            slots_bytes += slot_bytes_for(cap, entry_bytes);
         }
 
         doc_recs.resize((size_t)D);
@@ -414,6 +433,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->stream = (hipStream_t)hip_stream;
     c->n_cus = n_cus; c->lds_limit = lds_limit; c->sample_lds = sample_lds;
     c->n_tiles = (int32_t)tiles.size();
+    c->packed = packed;
     {
         const size_t theta_lds = (((size_t)K * 4 + 15) & ~(size_t)15) + (size_t)mlda::kThetaLgTable * 8;
         const int per_cu = std::max(1, std::min(24, (int)(144 * 1024 / theta_lds)));
@@ -469,8 +489,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         e = hipGetLastError();
     }
     if (e == hipSuccess && sample_lds > 48 * 1024)
-        e = hipFuncSetAttribute(sample_waves_for(K) == 4 ? (const void*)mlda::sample_kernel<4>
-                                                         : (const void*)mlda::sample_kernel<16>,
+        e = hipFuncSetAttribute(sample_kernel_for(K, packed),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sample_lds);
     if (e == hipSuccess && (size_t)K * 4 > 48 * 1024) {
         e = hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
@@ -479,7 +498,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
             e = hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)mlda::theta_rows_kernel,
+            e = hipFuncSetAttribute(packed ? (const void*)mlda::theta_rows_kernel<true>
+                                           : (const void*)mlda::theta_rows_kernel<false>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     K * 4 + 16 + mlda::kThetaLgTable * 8);
     }
@@ -563,12 +583,11 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
             a.beta_V = c->beta * (double)c->V;
             a.seed = c->seed;
             a.iter = (uint32_t)(c->iter + 1);
-            if (sample_waves_for(c->K) == 4)
-                hipLaunchKernelGGL(mlda::sample_kernel<4>, dim3((unsigned)c->n_tiles),
-                                   dim3(4 * mlda::kWave), c->sample_lds, c->stream, a);
-            else
-                hipLaunchKernelGGL(mlda::sample_kernel<16>, dim3((unsigned)c->n_tiles),
-                                   dim3(16 * mlda::kWave), c->sample_lds, c->stream, a);
+            const int waves = sample_waves_for(c->K);
+            void* kernel_args[] = {&a};
+            HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->packed), dim3((unsigned)c->n_tiles),
+                                    dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds,
+                                    c->stream));
             rc = launch_check("sample_kernel");
             if (rc != MLDA_OK) return rc;
         }
@@ -667,8 +686,16 @@ int mlda_get_doc_topic_csr(mlda_ctx* c, int64_t* row_ptr, uint16_t* topics, int3
         const uint32_t nnz = rec[d].y, pad = (nnz + 3u) & ~3u;
         const unsigned char* base = slots.data() + (size_t)rec[d].x * 16;
         if (nnz == 0) continue;
-        std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
-        std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
+        if (c->packed) {
+            const uint32_t* ent = reinterpret_cast<const uint32_t*>(base);
+            for (uint32_t j = 0; j < nnz; ++j) {
+                counts[row_ptr[d] + j] = (int32_t)(ent[j] >> 18);
+                topics[row_ptr[d] + j] = (uint16_t)((ent[j] >> 2) & 0xffffu);
+            }
+        } else {
+            std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
+            std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
+        }
     }
     return MLDA_OK;
 }
@@ -719,7 +746,8 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
         const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
         // per token: document id 4, token id 4, old topic 2, new topic 2, row record 8
-        bytes[i] = 20.0 * (double)c->T + 6.0 * row_entries + 4.0 * (double)c->K * (double)c->n_tiles;
+        bytes[i] = 20.0 * (double)c->T + (c->packed ? 4.0 : 6.0) * row_entries +
+                   4.0 * (double)c->K * (double)c->n_tiles;
     }
     *n_iters = n;
     return MLDA_OK;

@@ -113,6 +113,9 @@ EDGE_CASES = [
     ("one_word_vocab",      40,  1,    8,   20),
     ("large_k_small_docs",  300, 2000, 10000, 120),   # C5-like K: 45 KB of LDS per tile
     ("short_docs",          3000, 200, 16,  1.2),     # many single-token documents (S = 0)
+    # documents of 2^14 tokens or more: the library falls back to 6-byte theta entries
+    ("huge_docs_split_rows", 3,   400,  700, 17000),
+    ("huge_docs_few_topics", 4,   50,   24,  16500),
 ]
 
 
@@ -217,7 +220,8 @@ def test_step_with_loglik_flag_and_timing(mlda):
                                                 cfg.beta, SEED, 5), cfg.K)[0]
     got = model.sampler_bytes()
     for row_ptr, b in zip((before, mid), got):
-        want = 20.0 * c.T + 6.0 * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
+        entry_bytes = 4.0 if lens.max() < 2**14 else 6.0       # packed theta entries when counts fit 14 bits
+        want = 20.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
         assert b == want
     assert len(got) == 2
     model.close()
