@@ -117,6 +117,7 @@ __device__ __forceinline__ double lgamma_large(double x) {
 // Counts of a theta row are small: the rebuild keeps only this many table entries in LDS
 // (occupancy matters more there) and reads the rest of the table from global memory.
 constexpr int kThetaLgTable = 128;
+constexpr int kXcds = 8;            // accelerator dies of an MI355X, each with its own L2
 
 // One document as the theta rebuild needs it, stored in processing order.
 struct __align__(16) DocRec {
@@ -164,7 +165,12 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     double ll = 0.0;
     const int64_t step = gridDim.x;
     const DocRec none = {0, 0, 0u, 0};
-    int64_t i = blockIdx.x;
+    // workgroups are dealt to the 8 XCDs round-robin: give each XCD a contiguous run of
+    // documents, so that neighbouring gathers meet in the same L2
+    const int per_xcd = (int)gridDim.x / kXcds;
+    int64_t i = (int)blockIdx.x < per_xcd * kXcds
+                    ? (int64_t)((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds
+                    : (int64_t)blockIdx.x;
     DocRec cur = i < D ? docs[i] : none;
     DocRec nxt = i + step < D ? docs[i + step] : none;
     int p0 = doc_token_position(doc_map, cur, lane);
