@@ -415,7 +415,18 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                                           n <= kPhiSegment ? 1 : 0});
         }
         auto larger_first = [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; };
-        std::stable_sort(tiles.begin(), tiles.end(), larger_first);
+        // Sampling tiles run in the order of their first document (longest documents first),
+        // not word by word: tiles of different words that are in flight together then walk the
+        // theta rows of the same documents, which are fetched from HBM once instead of once
+        // per heavy word.  (The paper issues the tiles of heavy words first, Section 6.1.2;
+        // here the long-row tiles come first, which also keeps the tail short.)
+        {
+            std::vector<int32_t> rank((size_t)D);
+            for (int64_t i = 0; i < D; ++i) rank[(size_t)doc_order[(size_t)i]] = (int32_t)i;
+            std::stable_sort(tiles.begin(), tiles.end(), [&](const mlda::Tile& a, const mlda::Tile& b) {
+                return rank[(size_t)tok_doc[(size_t)a.begin]] < rank[(size_t)tok_doc[(size_t)b.begin]];
+            });
+        }
         std::stable_sort(segs.begin(), segs.end(), larger_first);
     } catch (const std::bad_alloc&) {
         return fail(MLDA_ENOMEM, "out of host memory");
