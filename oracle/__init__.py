@@ -22,6 +22,9 @@ _CFLAGS = ["-O2", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fas
 
 
 def build(force: bool = False) -> str:
+    override = os.environ.get("LDA_ORACLE_LIB")     # the mutation test points at broken builds
+    if override:
+        return override
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", *_CFLAGS, "-o", _LIB, _SRC, "-lm"])
     return _LIB
@@ -33,35 +36,41 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        i64, i32, u64, u32, dbl = (ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
-                                   ctypes.c_uint32, ctypes.c_double)
-        p = ctypes.c_void_p
-        lib.oracle_philox4x32_10.restype = None
-        lib.oracle_philox4x32_10.argtypes = [p, p, p]
-        lib.oracle_uniform.restype = dbl
-        lib.oracle_uniform.argtypes = [u64, u32, u64]
-        lib.oracle_uniforms.restype = None
-        lib.oracle_uniforms.argtypes = [u64, u32, u64, i64, p]
-        lib.oracle_init_topics.restype = None
-        lib.oracle_init_topics.argtypes = [i64, i32, u64, p]
-        lib.oracle_count_word_topic.restype = None
-        lib.oracle_count_word_topic.argtypes = [i64, p, p, i32, i32, p, p]
-        lib.oracle_doc_topic_csr.restype = i64
-        lib.oracle_doc_topic_csr.argtypes = [i64, p, p, i32, p, p, p]
-        lib.oracle_resample_token.restype = i32
-        lib.oracle_resample_token.argtypes = [i32, i32, dbl, dbl, p, p, p, i32, dbl, p, p, p]
-        lib.oracle_iteration.restype = None
-        lib.oracle_iteration.argtypes = [i64, p, p, p, i32, i32, dbl, dbl, u64, u32, p, p, p,
-                                         ctypes.c_int]
-        lib.oracle_resample_listed.restype = None
-        lib.oracle_resample_listed.argtypes = [i64, p, p, p, p, p, i32, i32, dbl, dbl, u64, u32,
-                                               p, p, p]
-        lib.oracle_loglik.restype = dbl
-        lib.oracle_loglik.argtypes = [i64, p, p, i32, i32, dbl, dbl, p, p]
-        lib.oracle_max_threads.restype = ctypes.c_int
-        _lib = lib
+        _lib = bind(build())
     return _lib
+
+
+def bind(path: str):
+    """Load an oracle library from `path` and declare its signatures (the mutation test
+    binds deliberately broken builds this way)."""
+    lib = ctypes.CDLL(path)
+    i64, i32, u64, u32, dbl = (ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+                               ctypes.c_uint32, ctypes.c_double)
+    p = ctypes.c_void_p
+    lib.oracle_philox4x32_10.restype = None
+    lib.oracle_philox4x32_10.argtypes = [p, p, p]
+    lib.oracle_uniform.restype = dbl
+    lib.oracle_uniform.argtypes = [u64, u32, u64]
+    lib.oracle_uniforms.restype = None
+    lib.oracle_uniforms.argtypes = [u64, u32, u64, i64, p]
+    lib.oracle_init_topics.restype = None
+    lib.oracle_init_topics.argtypes = [i64, i32, u64, p]
+    lib.oracle_count_word_topic.restype = None
+    lib.oracle_count_word_topic.argtypes = [i64, p, p, i32, i32, p, p]
+    lib.oracle_doc_topic_csr.restype = i64
+    lib.oracle_doc_topic_csr.argtypes = [i64, p, p, i32, p, p, p]
+    lib.oracle_resample_token.restype = i32
+    lib.oracle_resample_token.argtypes = [i32, i32, dbl, dbl, p, p, p, i32, dbl, p, p, p]
+    lib.oracle_iteration.restype = None
+    lib.oracle_iteration.argtypes = [i64, p, p, p, i32, i32, dbl, dbl, u64, u32, p, p, p,
+                                     ctypes.c_int]
+    lib.oracle_resample_listed.restype = None
+    lib.oracle_resample_listed.argtypes = [i64, p, p, p, p, p, i32, i32, dbl, dbl, u64, u32,
+                                           p, p, p]
+    lib.oracle_loglik.restype = dbl
+    lib.oracle_loglik.argtypes = [i64, p, p, i32, i32, dbl, dbl, p, p]
+    lib.oracle_max_threads.restype = ctypes.c_int
+    return lib
 
 
 def _c(a, dtype):
