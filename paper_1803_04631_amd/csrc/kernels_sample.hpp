@@ -55,6 +55,8 @@ struct SampleArgs {
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
 constexpr int kKeptQuads = 2;   // quads (of four entries) a lane keeps in registers at most
 
+// Once a token's pass has read its record, the record takes the result back to the per-lane
+// phase: the new topic (or -1 for "dense bucket") in `off`, the dense draw position in `u`.
 struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
     uint32_t off;               // slot offset of the token's theta row, 16-byte units
     int32_t nnz;
@@ -67,7 +69,7 @@ struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
 // LDS bytes of sample_kernel<kWaves> for a given Kpad.
 __host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
     return (size_t)Kpad * 4 + (size_t)((Kpad / kGroup + 1) & ~1) * 8 +
-           (size_t)waves * kWave * (8 + sizeof(TokenRec) + 4);
+           (size_t)waves * kWave * sizeof(TokenRec);
 }
 
 // Dense bucket (p2 = alpha p*', Eq. 6): smallest k with alpha * prefix'(k) > y, where
@@ -255,11 +257,11 @@ __device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, in
 }
 
 __device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int k_sel,
-                                          int* my_res, double* my_y) {
-    if (d.hit) my_res[r.ti] = k_sel;
+                                          TokenRec* my_rec) {
+    if (d.hit) my_rec[r.ti].off = (uint32_t)k_sel;
     if (r.row_on && !d.sparse && r.sl == 0) {
-        my_res[r.ti] = -1;                  // the draw falls into the dense bucket p2
-        my_y[r.ti] = d.x - d.S;
+        my_rec[r.ti].off = 0xffffffffu;     // the draw falls into the dense bucket p2
+        my_rec[r.ti].u = d.x - d.S;
     }
 }
 
@@ -267,8 +269,7 @@ __device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int
 // sums in registers, and the entries as loaded.
 template <class Layout, int kLanes, int kQuads>
 __device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename Layout::Raw* raw,
-                                              const float* pstar, int lane, int* my_res,
-                                              double* my_y) {
+                                              const float* pstar, int lane, TokenRec* my_rec) {
     QuadSums q[kQuads];
     double acc = 0.0;
 #pragma unroll
@@ -292,15 +293,14 @@ __device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename La
             }
         }
     }
-    row_store(r, d, Layout::template topic_of<kQuads>(raw, sel), my_res, my_y);
+    row_store(r, d, Layout::template topic_of<kQuads>(raw, sel), my_rec);
 }
 
 // Rows of more than 512 entries, one per wave: one walk for the sums, a second one over the
 // hit lane's entries.
 template <class Layout>
 __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int K,
-                                              const float* pstar, int lane, int* my_res,
-                                              double* my_y) {
+                                              const float* pstar, int lane, TokenRec* my_rec) {
     const int e0 = r.sl * 4 * r.n4;
     double acc = 0.0;
     for (int c = 0; c < r.n4; ++c) {
@@ -329,7 +329,7 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const 
         }
         if (!ok) k_sel = last_k;
     }
-    row_store(r, d, k_sel, my_res, my_y);
+    row_store(r, d, k_sel, my_rec);
 }
 
 template <int kWaves, class Layout>
@@ -344,10 +344,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     const int tid = (int)threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);      // wave-uniform, in an SGPR
     unsigned char* wave_base = lds + (size_t)Kpad * 4 + (size_t)((ng + 1) & ~1) * 8;
-    double* my_y = reinterpret_cast<double*>(wave_base) + wave * kWave;
-    TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base + (size_t)kWaves * kWave * 8) + wave * kWave;
-    int* my_res = reinterpret_cast<int*>(wave_base + (size_t)kWaves * kWave * (8 + sizeof(TokenRec))) +
-                  wave * kWave;
+    TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base) + wave * kWave;
 
     Tile tl = a.tiles[blockIdx.x];         // the same for every lane: keep it in SGPRs
     tl.word = __builtin_amdgcn_readfirstlane(tl.word);
@@ -468,15 +465,15 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             }
             if (lanes == 16) {
                 if (((over64 >> t_cur) & 0xfull) == 0)
-                    row_pass_kept<Layout, 16, 1>(r, mine_raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<Layout, 16, 1>(r, mine_raw, pstar, lane, my_rec);
                 else
-                    row_pass_kept<Layout, 16, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                    row_pass_kept<Layout, 16, 2>(r, mine_raw, pstar, lane, my_rec);
             } else if (lanes == 32) {
-                row_pass_kept<Layout, 32, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                row_pass_kept<Layout, 32, 2>(r, mine_raw, pstar, lane, my_rec);
             } else if (((over512 >> t_cur) & 1ull) == 0) {
-                row_pass_kept<Layout, 64, 2>(r, mine_raw, pstar, lane, my_res, my_y);
+                row_pass_kept<Layout, 64, 2>(r, mine_raw, pstar, lane, my_rec);
             } else {
-                row_pass_long<Layout>(a.slots, r, K, pstar, lane, my_res, my_y);
+                row_pass_long<Layout>(a.slots, r, K, pstar, lane, my_rec);
             }
         };
         Raw raw_a[kKeptQuads], raw_b[kKeptQuads];
@@ -491,9 +488,9 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
 
         // ---- one token per lane again: dense bucket, store
         if (valid) {
-            int z_new = my_res[lane];
+            int z_new = (int)my_rec[lane].off;
             if (z_new < 0)
-                z_new = dense_bucket_search(pstar, cp, K, ng, a.alpha, my_y[lane], mine.o, mine.w_o,
+                z_new = dense_bucket_search(pstar, cp, K, ng, a.alpha, my_rec[lane].u, mine.o, mine.w_o,
                                             delta);
             a.z_next[pos] = (uint16_t)z_new;
         }
