@@ -132,6 +132,18 @@ __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const 
     return j < r.n ? doc_map[r.begin + j] : -1;
 }
 
+// LDS bytes of the rebuild's dense row.  Rows with 4-byte entries hold counts below 2^14:
+// two 16-bit counters per dword plus one bit per topic that marks the non-zero bins.  Rows
+// with 6-byte entries keep one int32 counter per topic.
+__host__ __device__ inline size_t theta_hist_bytes(int32_t K, bool packed) {
+    const size_t counters = packed ? (size_t)((K + 1) / 2) * 4 : (size_t)K * 4;
+    const size_t marks = packed ? (size_t)((K + 31) / 32) * 4 : 0;
+    return ((counters + 15) & ~(size_t)15) + ((marks + 15) & ~(size_t)15);
+}
+__host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool packed) {
+    return theta_hist_bytes(K, packed) + (size_t)kThetaLgTable * 8;
+}
+
 // Update theta (Section 6.2): document by document, (1) a dense K-long histogram of the
 // document's assignments, reached through the document->token map, (2) compaction of the
 // non-zero bins into the row (topics ascending).  One wave per document, persistent; the
@@ -142,6 +154,8 @@ __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const 
 // gathered, the map entries of the wave's next document and the record of the one after are
 // already on their way.  Rows are written in the layout the sampler reads (SplitRows or
 // PackedRows, see kernels_sample.hpp); padding entries hold count 0 and topic K.
+// With PackedRows the compaction visits only the 32-topic groups that hold a non-zero bin
+// (one mark bit per topic), so its cost follows the row's length rather than K.
 // While the counts pass through registers the kernel also adds up the theta entries' term of
 // the log-likelihood, sum_{d,k} lgG(n_dk + alpha) - lgG(alpha), one partial per workgroup.
 template <bool kPacked>
@@ -154,15 +168,38 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                                                            unsigned long long* row_entries,
                                                            double* ll_partial) {
     extern __shared__ __align__(16) unsigned char lds[];
-    int32_t* hist = reinterpret_cast<int32_t*>(lds);
-    double* table = reinterpret_cast<double*>(lds + (((size_t)K * 4 + 15) & ~(size_t)15));
+    // kPacked: `hist` holds (K+1)/2 dwords of paired 16-bit counters, `marks` one bit per topic
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
+    const int n_counters = kPacked ? (K + 1) / 2 : K;
+    const int n_marks = kPacked ? (K + 31) / 32 : 0;
+    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (((size_t)n_counters * 4 + 15) & ~(size_t)15));
+    double* table = reinterpret_cast<double*>(lds + theta_hist_bytes(K, kPacked));
     const int lane = (int)threadIdx.x;
     const double lg_alpha = lg_table[kLgTable];
-    for (int k = lane; k < K; k += kWave) hist[k] = 0;
+    for (int k = lane; k < n_counters; k += kWave) hist[k] = 0u;
+    for (int k = lane; k < n_marks; k += kWave) marks[k] = 0u;
     for (int c = lane; c < kThetaLgTable; c += kWave) table[c] = lg_table[c];
     __syncthreads();
     unsigned long long visited = 0;      // sum of N_d * nnz_d over this wave's documents
     double ll = 0.0;
+    // lgG(c + alpha) - lgG(alpha) added to `ll`; the rare large counts go through a branch the
+    // whole wave takes or skips, so that the common case never pays for the logarithm
+    auto add_ll = [&](int c) {
+        if (c > 0 && c < kThetaLgTable) ll += table[c];
+        if (__ballot(c >= kThetaLgTable) != 0) {
+            if (c >= kThetaLgTable)
+                ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
+        }
+    };
+    // one more token of topic k in the dense row; returns 1 if it is the topic's first
+    auto count_topic = [&](int k) -> int {
+        if (kPacked) {
+            atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
+            atomicOr(&marks[k >> 5], 1u << (k & 31));
+            return 0;                     // the row's length comes from the marks instead
+        }
+        return atomicAdd(&hist[k], 1u) == 0u ? 1 : 0;
+    };
     const int64_t step = gridDim.x;
     const DocRec none = {0, 0, 0u, 0};
     // workgroups are dealt to the 8 XCDs round-robin: give each XCD a contiguous run of
@@ -185,45 +222,70 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         const DocRec after = i + 2 * step < D ? docs[i + 2 * step] : none;
 
         int fresh = 0;                    // first token of a topic
-        if (k0 >= 0) fresh += (atomicAdd(&hist[k0], 1) == 0) ? 1 : 0;
-        if (k1 >= 0) fresh += (atomicAdd(&hist[k1], 1) == 0) ? 1 : 0;
-        for (int j = 2 * kWave + lane; j < cur.n; j += kWave) {
-            const int k = (int)z[doc_map[cur.begin + j]];
-            fresh += (atomicAdd(&hist[k], 1) == 0) ? 1 : 0;
-        }
-        const int nnz = wave_sum(fresh);
+        if (k0 >= 0) fresh += count_topic(k0);
+        if (k1 >= 0) fresh += count_topic(k1);
+        for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
+            fresh += count_topic((int)z[doc_map[cur.begin + j]]);
         __syncthreads();
-        const int nnz_pad = (nnz + 3) & ~3;
-        // SplitRows: int32 counts then uint16 topics; PackedRows: uint32 count << 18 | topic << 2
-        int32_t* cnt = reinterpret_cast<int32_t*>(slots + (size_t)cur.slot * 16u);
-        uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
-        uint32_t* ent = reinterpret_cast<uint32_t*>(cnt);
-        int filled = 0;
-        for (int base = 0; base < K; base += kWave) {
-            const int k = base + lane;
-            const int c = (k < K) ? hist[k] : 0;
-            const uint64_t m = __ballot(c > 0);
-            if (m == 0) continue;
-            if (c > 0) {
-                const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
-                if (kPacked) {
-                    ent[at] = ((uint32_t)c << 18) | ((uint32_t)k << 2);
-                } else {
+        int nnz;
+        unsigned char* slot = slots + (size_t)cur.slot * 16u;
+        if constexpr (kPacked) {
+            // uint32 entries count << 18 | topic << 2.  Each lane owns one word of marks
+            // (32 topics = 16 counter pairs) and writes its non-zero bins in ascending order
+            // behind those of the lanes below it.
+            uint32_t* ent = reinterpret_cast<uint32_t*>(slot);
+            int filled = 0;
+            for (int base = 0; base < n_marks; base += kWave) {
+                const int wi = base + lane;
+                const uint32_t w = wi < n_marks ? marks[wi] : 0u;
+                if (__ballot(w != 0u) == 0) continue;
+                const int mine = __popc(w);
+                const int upto = wave_inclusive_sum(mine);
+                int at = filled + upto - mine;
+                filled += read_lane(upto, kWave - 1);
+                if (w != 0u) marks[wi] = 0u;
+                uint32_t pairs = (w | (w >> 1)) & 0x55555555u;
+                while (__ballot(pairs != 0u) != 0) {
+                    int lo = 0, hi = 0;
+                    if (pairs != 0u) {
+                        const int k = wi * 32 + __ffs((int)pairs) - 1;    // even topic of the pair
+                        pairs &= pairs - 1u;
+                        const uint32_t both = hist[k >> 1];
+                        hist[k >> 1] = 0u;
+                        lo = (int)(both & 0xffffu);
+                        hi = (int)(both >> 16);
+                        if (lo != 0) ent[at++] = ((uint32_t)lo << 18) | ((uint32_t)k << 2);
+                        if (hi != 0) ent[at++] = ((uint32_t)hi << 18) | ((uint32_t)(k + 1) << 2);
+                    }
+                    add_ll(lo);
+                    add_ll(hi);
+                }
+            }
+            nnz = filled;
+            const int nnz_pad = (nnz + 3) & ~3;
+            if (lane < nnz_pad - nnz) ent[nnz + lane] = (uint32_t)K << 2;
+        } else {
+            // int32 counts[round4(nnz)], then uint16 topics
+            nnz = wave_sum(fresh);
+            const int nnz_pad = (nnz + 3) & ~3;
+            int32_t* cnt = reinterpret_cast<int32_t*>(slot);
+            uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
+            int filled = 0;
+            for (int base = 0; base < K; base += kWave) {
+                const int k = base + lane;
+                const int c = (k < K) ? (int)hist[k] : 0;
+                const uint64_t m = __ballot(c > 0);
+                if (m == 0) continue;
+                if (c > 0) {
+                    const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
                     cnt[at] = c;
                     top[at] = (uint16_t)k;
+                    hist[k] = 0u;
                 }
-                hist[k] = 0;
-                if (c < kThetaLgTable) ll += table[c];
+                add_ll(c);
+                filled += __popcll((unsigned long long)m);
             }
-            if (__ballot(c >= kThetaLgTable) != 0) {  // rare: taken by the whole wave or not at all
-                if (c >= kThetaLgTable)
-                    ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
-            }
-            filled += __popcll((unsigned long long)m);
-        }
-        if (lane < nnz_pad - nnz) {
-            if (kPacked) ent[nnz + lane] = (uint32_t)K << 2;
-            else { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
+            if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
         }
         if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;
         visited += (unsigned long long)cur.n * (unsigned long long)nnz;

@@ -186,7 +186,7 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
     }
     if (ev_phi) HIP_TRY(hipEventRecord(*ev_phi, c->stream));
     if (c->D > 0) {
-        const size_t theta_lds = ((hist_bytes + 15) & ~(size_t)15) + (size_t)kThetaLgTable * 8;
+        const size_t theta_lds = theta_lds_bytes(c->K, c->packed);
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
         if (c->packed)
@@ -446,7 +446,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->n_tiles = (int32_t)tiles.size();
     c->packed = packed;
     {
-        const size_t theta_lds = (((size_t)K * 4 + 15) & ~(size_t)15) + (size_t)mlda::kThetaLgTable * 8;
+        const size_t theta_lds = mlda::theta_lds_bytes(K, packed);
         const int per_cu = std::max(1, std::min(24, (int)(144 * 1024 / theta_lds)));
         c->theta_grid = (int32_t)std::min<int64_t>({D, (int64_t)n_cus * per_cu, (int64_t)kMaxThetaGrid});
     }
@@ -512,7 +512,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
             e = hipFuncSetAttribute(packed ? (const void*)mlda::theta_rows_kernel<true>
                                            : (const void*)mlda::theta_rows_kernel<false>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    K * 4 + 16 + mlda::kThetaLgTable * 8);
+                                    (int)mlda::theta_lds_bytes(K, packed));
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
