@@ -12,14 +12,17 @@
 //     p*(o), and the search in the dense bucket p2 (binary search over the group prefixes,
 //     then at most 16 steps);
 //   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
-//     by a GROUP of 16, 32 or 64 lanes per token (one, two or four DPP rows), chosen per pass
-//     from the row lengths so that a lane owns at most eight entries: every lane owns a
-//     contiguous run of entries, loaded four at a time as one 16-byte and one 8-byte load,
-//     accumulates them in fp64 in registers, and a DPP scan over the group gives the prefix
-//     over lanes.  The lane whose range holds the draw finds "the smallest k whose prefix
-//     exceeds it" (Section 6.1.1) among its own entries.  Rows of more than 512 entries are
-//     walked twice by a whole wave.  Token parameters and results travel between the
-//     per-lane and per-group phases through small per-wave LDS records;
+//     by a GROUP of 4, 8, 16, 32 or 64 lanes per token, chosen per pass from the row lengths
+//     so that a lane owns at most eight entries (16, 8, 4, 2 or 1 tokens per pass: the fixed
+//     cost of a pass is shared by as many tokens as their rows allow).  Groups narrower than
+//     a DPP row of 16 lanes are interleaved inside the row (4 or 2 tokens side by side), so
+//     that plain row shifts scan every group at once.  Every lane owns a contiguous run of
+//     entries, loaded four at a time, accumulates them in fp64 in registers, and a DPP scan
+//     over the group gives the prefix over lanes.  The lane whose range holds the draw finds
+//     "the smallest k whose prefix exceeds it" (Section 6.1.1) among its own entries.  Rows
+//     of more than 512 entries are walked twice by a whole wave.  Token parameters and
+//     results travel between the per-lane and per-group phases through small per-wave LDS
+//     records;
 //   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
 //     loads of the next pass are issued before the current pass is worked on.
 #pragma once
@@ -105,39 +108,41 @@ __device__ __forceinline__ double dpp_move_all0(double v) {
     return __hiloint2double(hi, lo);
 }
 
-// Inclusive prefix sum inside each group of kLanes (16, 32 or 64) lanes.  Every lane must be
-// active.  Four shifts inside each row of 16 lanes; for wider groups lane 15 of the even
-// rows is added to the odd rows, and for the whole wave lane 31 to rows 2 and 3.
+// Lane layout of a pass with kLanes lanes per token.  Groups of 16, 32 or 64 lanes are runs
+// of consecutive lanes.  Groups of 8 or 4 lanes are interleaved inside each row of 16 lanes:
+// with g = 16 / kLanes tokens per row, lane l of the row works for token l % g as its
+// sub-lane l / g.
+//
+// Inclusive prefix sum over the sub-lanes of every group.  Every lane must be active.
+// Shifts inside each row of 16 lanes (starting at the interleave distance); for wider groups
+// lane 15 of the even rows is added to the odd rows, and for the whole wave lane 31 to rows
+// 2 and 3.
 template <int kLanes>
 __device__ __forceinline__ double group_inclusive_sum(double v) {
-    v += dpp_move_all0<0x111>(v);   // row_shr:1
-    v += dpp_move_all0<0x112>(v);   // row_shr:2
-    v += dpp_move_all0<0x114>(v);   // row_shr:4
-    v += dpp_move_all0<0x118>(v);   // row_shr:8
+    if (kLanes >= 16) v += dpp_move_all0<0x111>(v);   // row_shr:1
+    if (kLanes >= 8) v += dpp_move_all0<0x112>(v);    // row_shr:2
+    v += dpp_move_all0<0x114>(v);                      // row_shr:4
+    v += dpp_move_all0<0x118>(v);                      // row_shr:8
     if (kLanes >= 32) v += dpp_move0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
     if (kLanes >= 64) v += dpp_move0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
-// Value of the lane before this one inside the group, 0 for the group's first lane.
+// Value of the sub-lane before this one inside the group, 0 for the group's first sub-lane.
 template <int kLanes>
 __device__ __forceinline__ double group_previous(double incl, int sl) {
     if (kLanes == 16) return dpp_move_all0<0x111>(incl);          // row_shr:1
+    if (kLanes == 8) return dpp_move_all0<0x112>(incl);           // row_shr:2
+    if (kLanes == 4) return dpp_move_all0<0x114>(incl);           // row_shr:4
     const double up = dpp_move_all0<0x138>(incl);                  // wave_shr:1
     return sl == 0 ? 0.0 : up;
 }
 
-// What the lanes of a group need of their token.
-struct RowCtx {
-    uint32_t off;           // slot of the theta row, 16-byte units
-    int nnz, n4;            // n4 = quads each lane owns; lane sl owns entries [4 n4 sl, 4 n4 (sl+1))
-    int o_key;              // 4 * current topic (a topic's key is its byte offset in p*)
-    float w_o;
-    double u, Qp;
-    bool row_on;
-    int ti;                 // token index inside the wave's batch
-    int sl;                 // lane index inside the group
-};
+// Lane that holds the group's last sub-lane.
+template <int kLanes>
+__device__ __forceinline__ int group_last_lane(int lane) {
+    return kLanes >= 16 ? (lane | (kLanes - 1)) : (lane | (16 - 16 / kLanes));
+}
 
 // Layout of a theta row inside its slot, 6 bytes per entry: int32 counts[round4(nnz)] then
 // uint16 topics[round4(nnz)].  Always usable.
@@ -237,18 +242,33 @@ __device__ __forceinline__ QuadSums quad_sums(const typename Layout::Raw& raw, i
     return q;
 }
 
+// What the lanes of a group need of their token, read back from its record.
+struct RowCtx {
+    int o_key;              // 4 * current topic (a topic's key is its byte offset in p*)
+    float w_o;
+    double u, Qp;
+};
+
+__device__ __forceinline__ RowCtx row_ctx(const TokenRec* rec) {
+    const int2 ow = *reinterpret_cast<const int2*>(&rec->o);
+    const double2 uq = *reinterpret_cast<const double2*>(&rec->u);
+    RowCtx r;
+    r.o_key = ow.x << 2; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
+    return r;
+}
+
 // Row total S (Eq. 7), the draw x = u (S + Q'), and whether this lane's entries hold it.
 struct RowDraw {
-    double S, x, y;         // y = x - (sum of the group's lanes before this one)
+    double S, x, y;         // y = x - (sum of the group's sub-lanes before this one)
     bool sparse, hit;
 };
 
 template <int kLanes>
-__device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, int lane) {
+__device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, int sl, int lane) {
     RowDraw d;
     const double incl = group_inclusive_sum<kLanes>(lane_sum);
-    const double excl = group_previous<kLanes>(incl, r.sl);
-    d.S = __shfl(incl, lane | (kLanes - 1), kWave);
+    const double excl = group_previous<kLanes>(incl, sl);
+    d.S = __shfl(incl, group_last_lane<kLanes>(lane), kWave);
     d.x = r.u * (d.S + r.Qp);
     d.sparse = d.x < d.S;
     d.hit = d.sparse && (incl > d.x) && !(excl > d.x);
@@ -256,20 +276,22 @@ __device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, in
     return d;
 }
 
-__device__ __forceinline__ void row_store(const RowCtx& r, const RowDraw& d, int k_sel,
-                                          TokenRec* my_rec) {
-    if (d.hit) my_rec[r.ti].off = (uint32_t)k_sel;
-    if (r.row_on && !d.sparse && r.sl == 0) {
-        my_rec[r.ti].off = 0xffffffffu;     // the draw falls into the dense bucket p2
-        my_rec[r.ti].u = d.x - d.S;
+// The result goes back in the token's record.  Records of a batch's unused tail take part
+// like any other (their rows are empty): what is written there is never read.
+__device__ __forceinline__ void row_store(TokenRec* rec, int sl, const RowDraw& d, int k_sel) {
+    if (d.hit) rec->off = (uint32_t)k_sel;
+    if (!d.sparse && sl == 0) {
+        rec->off = 0xffffffffu;             // the draw falls into the dense bucket p2
+        rec->u = d.x - d.S;
     }
 }
 
-// Rows whose lanes own at most kQuads quads, already loaded: every lane keeps its prefix
+// Rows whose sub-lanes own at most kQuads quads, already loaded: every lane keeps its prefix
 // sums in registers, and the entries as loaded.
 template <class Layout, int kLanes, int kQuads>
-__device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename Layout::Raw* raw,
-                                              const float* pstar, int lane, TokenRec* my_rec) {
+__device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, const typename Layout::Raw* raw,
+                                              const float* pstar, int lane) {
+    const RowCtx r = row_ctx(rec);
     QuadSums q[kQuads];
     double acc = 0.0;
 #pragma unroll
@@ -277,7 +299,7 @@ __device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename La
         q[c] = quad_sums<Layout>(raw[c], r.o_key, r.w_o, pstar, acc);
         acc = q[c].s[3];
     }
-    const RowDraw d = row_draw<kLanes>(acc, r, lane);
+    const RowDraw d = row_draw<kLanes>(acc, r, sl, lane);
     // smallest entry whose prefix exceeds y (the prefixes never decrease)
     uint32_t sel = Layout::handle(raw, 4 * kQuads - 1);
 #pragma unroll
@@ -293,31 +315,35 @@ __device__ __forceinline__ void row_pass_kept(const RowCtx& r, const typename La
             }
         }
     }
-    row_store(r, d, Layout::template topic_of<kQuads>(raw, sel), my_rec);
+    row_store(rec, sl, d, Layout::template topic_of<kQuads>(raw, sel));
 }
 
-// Rows of more than 512 entries, one per wave: one walk for the sums, a second one over the
-// hit lane's entries.
+// Rows of more than 512 entries, one per wave (sub-lane = lane): one walk for the sums, a
+// second one over the hit lane's entries.  Lane l owns the entries [4 n4 l, 4 n4 (l + 1)).
 template <class Layout>
-__device__ __forceinline__ void row_pass_long(const unsigned char* slots, const RowCtx& r, int K,
-                                              const float* pstar, int lane, TokenRec* my_rec) {
-    const int e0 = r.sl * 4 * r.n4;
+__device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenRec* rec, int K,
+                                              const float* pstar, int lane) {
+    const uint2 where = *reinterpret_cast<const uint2*>(rec);
+    const uint32_t off = where.x;
+    const int nnz = (int)where.y, n4 = (nnz + 4 * kWave - 1) / (4 * kWave);
+    const RowCtx r = row_ctx(rec);
+    const int e0 = lane * 4 * n4;
     double acc = 0.0;
-    for (int c = 0; c < r.n4; ++c) {
+    for (int c = 0; c < n4; ++c) {
         const int e = e0 + 4 * c;
-        const QuadSums q = quad_sums<Layout>(Layout::load(slots, r.off, r.nnz, e, e < r.nnz, K),
+        const QuadSums q = quad_sums<Layout>(Layout::load(slots, off, nnz, e, e < nnz, K),
                                              r.o_key, r.w_o, pstar, acc);
         acc = q.s[3];
     }
-    const RowDraw d = row_draw<kWave>(acc, r, lane);
+    const RowDraw d = row_draw<kWave>(acc, r, lane, lane);
     int k_sel = 0;
     if (__ballot(d.hit) != 0) {
         bool ok = false;
         int last_k = 0;
         acc = 0.0;
-        for (int c = 0; c < r.n4; ++c) {
+        for (int c = 0; c < n4; ++c) {
             const int e = e0 + 4 * c;
-            const typename Layout::Raw raw = Layout::load(slots, r.off, r.nnz, e, d.hit && e < r.nnz, K);
+            const typename Layout::Raw raw = Layout::load(slots, off, nnz, e, d.hit && e < nnz, K);
             const QuadSums q = quad_sums<Layout>(raw, r.o_key, r.w_o, pstar, acc);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -329,7 +355,7 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, const 
         }
         if (!ok) k_sel = last_k;
     }
-    row_store(r, d, k_sel, my_rec);
+    row_store(rec, lane, d, k_sel);
 }
 
 template <int kWaves, class Layout>
@@ -407,77 +433,67 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- one token per group of 16 / 32 / 64 lanes.  A pass takes the next 4, 2 or 1
-        // tokens, whichever lets every lane own at most kKeptQuads quads; the rows of the
+        // ---- one token per group of 4 .. 64 lanes.  A pass takes the next 16, 8, 4, 2 or 1
+        // tokens, as many as lets every lane own at most kKeptQuads quads; the rows of the
         // following pass are requested from memory before this one is worked on.
         const int n_here = min(kWave, tl.count - b * kWave);
-        // which tokens of the batch have rows beyond 64 / 128 / 256 / 512 entries (lanes past
-        // the batch's end hold nnz = 0): the shape of every pass follows from these masks
-        const uint64_t over64 = __ballot(mine.nnz > 16 * 4), over128 = __ballot(mine.nnz > 16 * 8);
-        const uint64_t over256 = __ballot(mine.nnz > 32 * 8), over512 = __ballot(mine.nnz > 64 * 8);
+        // which tokens of the batch have rows beyond 16 .. 512 entries (lanes past the batch's
+        // end hold nnz = 0): the shape of every pass follows from these masks
         static_assert(kKeptQuads == 2, "the pass shapes assume two kept quads per lane");
-        auto lanes_for = [&](int t0) {               // group width of the pass starting at t0
-            return ((over128 >> t0) & 0xfull) == 0 ? 16 : ((over256 >> t0) & 0x3ull) == 0 ? 32 : 64;
+        const uint64_t over16 = __ballot(mine.nnz > 16), over32 = __ballot(mine.nnz > 32);
+        const uint64_t over64 = __ballot(mine.nnz > 64), over128 = __ballot(mine.nnz > 128);
+        const uint64_t over256 = __ballot(mine.nnz > 256), over512 = __ballot(mine.nnz > 512);
+        // shape of the pass that starts at token t0: 0 = 4 lanes per token and one quad per
+        // lane, 1 .. 5 = 4, 8, 16, 32, 64 lanes and two quads, 6 = a row for the long walk
+        auto shape_at = [&](int t0) {
+            if (((over32 >> t0) & 0xffffull) == 0) return ((over16 >> t0) & 0xffffull) == 0 ? 0 : 1;
+            if (((over64 >> t0) & 0xffull) == 0) return 2;
+            if (((over128 >> t0) & 0xfull) == 0) return 3;
+            if (((over256 >> t0) & 0x3ull) == 0) return 4;
+            return ((over512 >> t0) & 0x1ull) == 0 ? 5 : 6;
         };
-        // where a pass's rows are, and the loads of the quads its lanes keep (lanes = 16, 32, 64)
+        auto lanes_log2 = [](int shape) { return shape <= 1 ? 2 : shape >= 5 ? 6 : shape + 1; };
+        // where a pass's rows are, and the loads of the quads its lanes keep.  `rec` is the
+        // record of the lane's token, `sl` the lane's place inside its group.  A pass that
+        // would run past the batch's 64 records works on the last one several times over.
         using Raw = typename Layout::Raw;
-        auto request = [&](int t0, int lanes, uint32_t& off, int& nnz, Raw* raw) {
-            const int shift = lanes == 16 ? 4 : lanes == 32 ? 5 : 6;
-            const int ti = t0 + (lane >> shift);
-            const bool on = ti < n_here;
-            const uint2 where = *reinterpret_cast<const uint2*>(&my_rec[on ? ti : 0]);
-            off = where.x;
-            nnz = on ? (int)where.y : 0;
-            const int n4 = (nnz + 4 * lanes - 1) >> (shift + 2);
-            const bool kept = n4 <= kKeptQuads;        // longer rows are loaded by their own walk
-#pragma unroll
-            for (int c = 0; c < kKeptQuads; ++c) {
-                const int e = (lane & (lanes - 1)) * 4 * n4 + 4 * c;
-                raw[c] = Layout::load(a.slots, off, nnz, e, kept && c < n4 && e < nnz, K);
-            }
+        auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, Raw* raw) {
+            const int lg = lanes_log2(shape);
+            const int g = lg < 4 ? 4 - lg : 0, hs = lg < 4 ? 4 : lg;    // interleave, run length
+            const int rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
+            sl = (lane & ((1 << hs) - 1)) >> g;
+            rec = my_rec + min(t0 + rel, kWave - 1);
+            const uint2 where = *reinterpret_cast<const uint2*>(rec);
+            const int nnz = (int)where.y;
+            const int e0 = shape == 0 ? sl * 4 : sl * 8;
+            raw[0] = Layout::load(a.slots, where.x, nnz, e0, shape != 6 && e0 < nnz, K);
+            raw[1] = Layout::load(a.slots, where.x, nnz, e0 + 4,
+                                  shape != 6 && shape != 0 && e0 + 4 < nnz, K);
         };
-        auto row_ctx = [&](int t0, int lanes, uint32_t off, int nnz) {
-            const int shift = lanes == 16 ? 4 : lanes == 32 ? 5 : 6;
-            RowCtx r;
-            r.sl = lane & (lanes - 1);
-            r.ti = t0 + (lane >> shift);
-            r.row_on = r.ti < n_here;
-            r.off = off;
-            r.nnz = nnz;
-            r.n4 = (nnz + 4 * lanes - 1) >> (shift + 2);
-            const TokenRec* rec = &my_rec[r.row_on ? r.ti : 0];
-            const int2 ow = *reinterpret_cast<const int2*>(&rec->o);
-            const double2 uq = *reinterpret_cast<const double2*>(&rec->u);
-            r.o_key = ow.x << 2; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
-            return r;
-        };
-        int t_next = 0, lanes_next = lanes_for(0), nnz_next;
-        uint32_t off_next;
+        int t_next = 0, shape_next = shape_at(0), sl_next;
+        TokenRec* rec_next;
         // one pass: `mine_raw` holds its rows, already requested; the following pass's rows
         // go to `next_raw`.  The two buffers swap roles from pass to pass.
         auto pass = [&](Raw* mine_raw, Raw* next_raw) {
-            const int lanes = lanes_next, t_cur = t_next;
-            const RowCtx r = row_ctx(t_cur, lanes, off_next, nnz_next);
-            t_next += lanes == 16 ? 4 : lanes == 32 ? 2 : 1;
+            const int shape = shape_next, sl = sl_next;
+            TokenRec* rec = rec_next;
+            t_next += kWave >> lanes_log2(shape);
             if (t_next < n_here) {
-                lanes_next = lanes_for(t_next);
-                request(t_next, lanes_next, off_next, nnz_next, next_raw);
+                shape_next = shape_at(t_next);
+                request(t_next, shape_next, rec_next, sl_next, next_raw);
             }
-            if (lanes == 16) {
-                if (((over64 >> t_cur) & 0xfull) == 0)
-                    row_pass_kept<Layout, 16, 1>(r, mine_raw, pstar, lane, my_rec);
-                else
-                    row_pass_kept<Layout, 16, 2>(r, mine_raw, pstar, lane, my_rec);
-            } else if (lanes == 32) {
-                row_pass_kept<Layout, 32, 2>(r, mine_raw, pstar, lane, my_rec);
-            } else if (((over512 >> t_cur) & 1ull) == 0) {
-                row_pass_kept<Layout, 64, 2>(r, mine_raw, pstar, lane, my_rec);
-            } else {
-                row_pass_long<Layout>(a.slots, r, K, pstar, lane, my_rec);
+            switch (shape) {
+            case 0: row_pass_kept<Layout, 4, 1>(rec, sl, mine_raw, pstar, lane); break;
+            case 1: row_pass_kept<Layout, 4, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 2: row_pass_kept<Layout, 8, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 3: row_pass_kept<Layout, 16, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 4: row_pass_kept<Layout, 32, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 5: row_pass_kept<Layout, 64, 2>(rec, sl, mine_raw, pstar, lane); break;
+            default: row_pass_long<Layout>(a.slots, rec, K, pstar, lane); break;
             }
         };
         Raw raw_a[kKeptQuads], raw_b[kKeptQuads];
-        request(0, lanes_next, off_next, nnz_next, raw_a);
+        request(0, shape_next, rec_next, sl_next, raw_a);
         while (t_next < n_here) {
             pass(raw_a, raw_b);
             if (t_next < n_here) pass(raw_b, raw_a);
