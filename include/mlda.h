@@ -130,8 +130,8 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
 
 /*
  * Algorithmic bytes each sampling launch of the most recent mlda_step had to move
- * (Section 3.1's accounting, with p* shared per word tile): per token 20 bytes (document
- * id, token id, old and new topic, row record) plus 4 bytes per entry of its theta row
+ * (Section 3.1's accounting, with p* shared per word tile): per token 16 bytes (slot of
+ * its theta row, token id, old and new topic, row length) plus 4 bytes per entry of its theta row
  * (6 if some document has 2^14 or more tokens: counts then need their own 32-bit words),
  * plus 4 K bytes of phi per tile.  bytes: host, capacity_iters doubles, out; rows as in
  * mlda_get_timing.

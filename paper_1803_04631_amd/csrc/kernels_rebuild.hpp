@@ -228,7 +228,8 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
             fresh += count_topic((int)z[doc_map[cur.begin + j]]);
         __syncthreads();
         int nnz;
-        unsigned char* slot = slots + (size_t)cur.slot * 16u;
+        unsigned char* head = slots + (size_t)cur.slot * 16u;
+        unsigned char* slot = head + kRowHeader;
         if constexpr (kPacked) {
             // uint32 entries count << 18 | topic << 2.  Each lane owns one word of marks
             // (32 topics = 16 counter pairs) and writes its non-zero bins in ascending order
@@ -287,7 +288,10 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
             }
             if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
         }
-        if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;
+        if (lane == 0) {                    // the row's length: in its slot for the sampler,
+            *reinterpret_cast<uint32_t*>(head) = (uint32_t)nnz;
+            row_rec[cur.doc].y = (uint32_t)nnz;      // and by document for the getters
+        }
         visited += (unsigned long long)cur.n * (unsigned long long)nnz;
         __syncthreads();
         cur = nxt; nxt = after; p0 = q0; p1 = q1;

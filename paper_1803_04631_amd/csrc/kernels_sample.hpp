@@ -39,13 +39,13 @@ struct Tile {          // consecutive word-major tokens of one word
 
 struct SampleArgs {
     const Tile* tiles;
-    const int32_t* tok_doc;     // [T] document of each word-major token
+    const uint32_t* tok_slot;   // [T] slot of the theta row of each word-major token's document
     const int32_t* tok_id;      // [T] its index in the caller's document-major order
     const uint16_t* z_cur;      // [T] word-major, frozen for the pass
     uint16_t* z_next;           // [T] word-major, written
-    const uint2* row_rec;       // [D] {slot offset in 16-byte units, nnz of the theta row}
-    // theta rows, in one of the two layouts below (SplitRows / PackedRows); padding entries
-    // hold count 0 and topic K
+    // theta rows: a slot (offset in 16-byte units) starts with a header of kRowHeader bytes
+    // whose first word is the row's length, then holds the entries in one of the two layouts
+    // below (SplitRows / PackedRows); padding entries hold count 0 and topic K
     const unsigned char* slots;
     const int32_t* n_wk;        // [V][K]
     const int32_t* n_k;         // [K]
@@ -55,6 +55,7 @@ struct SampleArgs {
     uint32_t iter;
 };
 
+constexpr int kRowHeader = 16;  // bytes before a theta row's entries
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
 constexpr int kKeptQuads = 2;   // quads (of four entries) a lane keeps in registers at most
 
@@ -158,7 +159,7 @@ struct SplitRows {
         q.c = make_int4(0, 0, 0, 0);
         q.t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
         if (on) {
-            const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)off * 16u);
+            const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)off * 16u + kRowHeader);
             const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz + 3) & ~3));
             q.c = *reinterpret_cast<const int4*>(cnt + e);
             q.t = *reinterpret_cast<const uint2*>(top + e);
@@ -198,7 +199,7 @@ struct PackedRows {
         q.e = make_uint4((uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2);
         if (on)
             q.e = *reinterpret_cast<const uint4*>(
-                reinterpret_cast<const uint32_t*>(slots + (size_t)off * 16u) + e);
+                reinterpret_cast<const uint32_t*>(slots + (size_t)off * 16u + kRowHeader) + e);
         return q;
     }
     static __device__ __forceinline__ uint32_t entry(const Raw& q, int j) {
@@ -415,12 +416,12 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         mine.off = 0; mine.nnz = 0; mine.o = 0; mine.w_o = 0.f; mine.u = 0.0; mine.Qp = 0.0;
         double delta = 0.0;
         if (valid) {
-            const int d = a.tok_doc[pos];
+            mine.off = a.tok_slot[pos];
             mine.o = (int)a.z_cur[pos];
             const uint64_t id = (uint64_t)(uint32_t)a.tok_id[pos];
-            const uint2 rec = a.row_rec[d];
-            mine.off = rec.x;
-            mine.nnz = (int)rec.y;
+            // the row's length sits in front of its entries: this read also brings the row's
+            // first line on its way
+            mine.nnz = *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
             mine.u = token_uniform(a.seed, a.iter, id);
             // the token itself is taken out of phi and n_k at its own topic
             mine.w_o = (float)(((double)(phi_v[mine.o] - 1) + a.beta) /

@@ -56,16 +56,18 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
 constexpr int kPhiSegment = 16384;    // tokens one workgroup histograms for the phi rebuild
 
+// A theta row's slot: a header of kRowHeader bytes (the row's length), then the entries.
 size_t slot_bytes_for(int64_t cap, int entry_bytes) {   // cap = largest nnz the row can reach
-    return align_up((size_t)(((cap + 3) & ~(int64_t)3) * entry_bytes), kSlotAlign);
+    return align_up((size_t)mlda::kRowHeader + (size_t)(((cap + 3) & ~(int64_t)3) * entry_bytes),
+                    kSlotAlign);
 }
 
 // Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
 struct Layout {
-    size_t tok_doc, tok_id, doc_map, z0, z1, doc_ptr, doc_order, row_rec, slots, n_wk, n_k, tiles, segs, split,
+    size_t tok_slot, tok_id, doc_map, z0, z1, doc_ptr, doc_order, row_rec, slots, n_wk, n_k, tiles, segs, split,
         ll_partial, ll_value, lg_table, row_entries, total;
     void finish() {
-        size_t* parts[] = {&tok_doc, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &doc_order, &row_rec, &slots,
+        size_t* parts[] = {&tok_slot, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &doc_order, &row_rec, &slots,
                            &n_wk, &n_k, &tiles, &segs, &split, &ll_partial, &ll_value, &lg_table, &row_entries};
         total = 0;
         for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
@@ -79,7 +81,7 @@ constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entri
 Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
                   size_t n_segs, size_t n_split) {
     Layout L{};
-    L.tok_doc = (size_t)T * 4;
+    L.tok_slot = (size_t)T * 4;
     L.tok_id = (size_t)T * 4;
     L.doc_map = (size_t)T * 4;
     L.z0 = (size_t)T * 2;
@@ -103,7 +105,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
 
 Layout layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
     const size_t tile = (size_t)tile_tokens_for(K);
-    const size_t slots = (size_t)T * 6 + (size_t)D * (18 + kSlotAlign);
+    const size_t slots = (size_t)T * 6 + (size_t)D * (mlda::kRowHeader + 18 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
     const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
     return layout_for(D, T, V, K, slots, n_tiles, n_segs, (size_t)V);
@@ -128,7 +130,8 @@ struct mlda_ctx {
     hipStream_t stream = nullptr;
     int n_cus = 0, lds_limit = 0;
 
-    int32_t *tok_doc = nullptr, *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    uint32_t* tok_slot = nullptr;         // [T] slot of the theta row of each word-major token's document
+    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
     mlda::DocRec* doc_order = nullptr;  // documents by falling length, as the theta rebuild walks them
     int32_t theta_grid = 0;
     bool packed = false;                // theta rows as 4-byte entries (no document has 2^14 tokens)
@@ -353,7 +356,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     for (int c = 0; c < n_chunks; ++c)
         if (chunk_bad[c]) return fail(MLDA_EINVAL, "word id outside [0, V)");
 
-    std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_doc, tok_id, doc_map, doc_ptr32, split_words;
+    std::vector<uint32_t> tok_slot;
+    std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_id, doc_map, doc_ptr32, split_words;
     std::vector<uint2> row_rec;
     std::vector<mlda::DocRec> doc_recs;
     std::vector<mlda::Tile> tiles, segs;
@@ -368,7 +372,18 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
             }
             word_ptr[v + 1] = word_ptr[v] + n;
         }
-        tok_doc.resize((size_t)T);
+        // ---- theta row slots: fixed capacity min(N_d, K), so rows never move; laid out in the
+        // order the documents are worked on, so that rows in use together are neighbours
+        row_rec.resize((size_t)D);
+        for (int64_t i = 0; i < D; ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
+            if (slots_bytes / 16 > 0xffffffffull)
+                return fail(MLDA_ENOTSUP, "theta rows need more than 64 GiB");
+            row_rec[(size_t)d] = make_uint2((uint32_t)(slots_bytes / 16), 0u);
+            slots_bytes += slot_bytes_for(cap, entry_bytes);
+        }
+        tok_slot.resize((size_t)T);
         tok_id.resize((size_t)T);
         doc_map.resize((size_t)T);
         parallel_chunks(n_chunks, [&](int c) {
@@ -379,22 +394,15 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                     const int32_t w = word_ids[t];
                     const int32_t pos = word_ptr[w] + start[w]++;
                     tok_id[pos] = (int32_t)t;
-                    tok_doc[pos] = (int32_t)d;
+                    tok_slot[pos] = row_rec[(size_t)d].x;
                     doc_map[t] = pos;
                 }
             }
         });
         chunk_hist.clear();
 
-        // ---- theta row slots: fixed capacity min(N_d, K), so rows never move
         doc_ptr32.resize((size_t)D + 1);
-        row_rec.resize((size_t)D);
         for (int64_t d = 0; d <= D; ++d) doc_ptr32[d] = (int32_t)doc_ptr[d];
-        for (int64_t d = 0; d < D; ++d) {
-            const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
-            row_rec[d] = make_uint2((uint32_t)(slots_bytes / 16), 0u);
-            slots_bytes += slot_bytes_for(cap, entry_bytes);
-        }
 
         doc_recs.resize((size_t)D);
         for (int64_t i = 0; i < D; ++i) {
@@ -420,13 +428,10 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         // theta rows of the same documents, which are fetched from HBM once instead of once
         // per heavy word.  (The paper issues the tiles of heavy words first, Section 6.1.2;
         // here the long-row tiles come first, which also keeps the tail short.)
-        {
-            std::vector<int32_t> rank((size_t)D);
-            for (int64_t i = 0; i < D; ++i) rank[(size_t)doc_order[(size_t)i]] = (int32_t)i;
-            std::stable_sort(tiles.begin(), tiles.end(), [&](const mlda::Tile& a, const mlda::Tile& b) {
-                return rank[(size_t)tok_doc[(size_t)a.begin]] < rank[(size_t)tok_doc[(size_t)b.begin]];
-            });
-        }
+        // (slot offsets rise in that order)
+        std::stable_sort(tiles.begin(), tiles.end(), [&](const mlda::Tile& a, const mlda::Tile& b) {
+            return tok_slot[(size_t)a.begin] < tok_slot[(size_t)b.begin];
+        });
         std::stable_sort(segs.begin(), segs.end(), larger_first);
     } catch (const std::bad_alloc&) {
         return fail(MLDA_ENOMEM, "out of host memory");
@@ -457,7 +462,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
 
     unsigned char* p = (unsigned char*)dev_workspace;
     auto take = [&](size_t bytes) { unsigned char* q = p; p += bytes; return q; };
-    c->tok_doc = (int32_t*)take(L.tok_doc);
+    c->tok_slot = (uint32_t*)take(L.tok_slot);
     c->tok_id = (int32_t*)take(L.tok_id);
     c->doc_map = (int32_t*)take(L.doc_map);
     c->z[0] = (uint16_t*)take(L.z0);
@@ -481,7 +486,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->stream);
     };
     hipError_t e = hipSuccess;
-    if (e == hipSuccess) e = up(c->tok_doc, tok_doc.data(), (size_t)T * 4);
+    if (e == hipSuccess) e = up(c->tok_slot, tok_slot.data(), (size_t)T * 4);
     if (e == hipSuccess) e = up(c->tok_id, tok_id.data(), (size_t)T * 4);
     if (e == hipSuccess) e = up(c->doc_map, doc_map.data(), (size_t)T * 4);
     if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
@@ -579,11 +584,10 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
         if (c->n_tiles > 0) {
             mlda::SampleArgs a;
             a.tiles = c->tiles;
-            a.tok_doc = c->tok_doc;
+            a.tok_slot = c->tok_slot;
             a.tok_id = c->tok_id;
             a.z_cur = c->z[c->cur];
             a.z_next = z_next;
-            a.row_rec = c->row_rec;
             a.slots = c->slots;
             a.n_wk = c->n_wk;
             a.n_k = c->n_k;
@@ -695,7 +699,7 @@ int mlda_get_doc_topic_csr(mlda_ctx* c, int64_t* row_ptr, uint16_t* topics, int3
     if (row_ptr[c->D] > 0 && (!topics || !counts)) return fail(MLDA_EINVAL, "topics or counts is null");
     for (int64_t d = 0; d < c->D; ++d) {
         const uint32_t nnz = rec[d].y, pad = (nnz + 3u) & ~3u;
-        const unsigned char* base = slots.data() + (size_t)rec[d].x * 16;
+        const unsigned char* base = slots.data() + (size_t)rec[d].x * 16 + mlda::kRowHeader;
         if (nnz == 0) continue;
         if (c->packed) {
             const uint32_t* ent = reinterpret_cast<const uint32_t*>(base);
@@ -756,8 +760,8 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
         const int32_t j = c->last_step_iters - n + i;
         const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
-        // per token: document id 4, token id 4, old topic 2, new topic 2, row record 8
-        bytes[i] = 20.0 * (double)c->T + (c->packed ? 4.0 : 6.0) * row_entries +
+        // per token: row slot 4, token id 4, old topic 2, new topic 2, row length 4
+        bytes[i] = 16.0 * (double)c->T + (c->packed ? 4.0 : 6.0) * row_entries +
                    4.0 * (double)c->K * (double)c->n_tiles;
     }
     *n_iters = n;

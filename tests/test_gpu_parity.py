@@ -221,7 +221,7 @@ def test_step_with_loglik_flag_and_timing(mlda):
     got = model.sampler_bytes()
     for row_ptr, b in zip((before, mid), got):
         entry_bytes = 4.0 if lens.max() < 2**14 else 6.0       # packed theta entries when counts fit 14 bits
-        want = 20.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
+        want = 16.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
         assert b == want
     assert len(got) == 2
     model.close()
