@@ -216,6 +216,13 @@ struct PackedRows {
     }
 };
 
+// p*(k) is staged at the very start of the workgroup's LDS, so a topic's key (4 k) is the
+// LDS address of its weight.
+__device__ __forceinline__ float lds_float_at(uint32_t byte_address) {
+    typedef __attribute__((address_space(3))) const float* lds_float_ptr;
+    return *(lds_float_ptr)(uintptr_t)byte_address;
+}
+
 // p1 = (count - [k = o]) * p*'(k), Eq. 6, accumulated onto `base`:
 // s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
 struct QuadSums {
@@ -231,7 +238,7 @@ __device__ __forceinline__ QuadSums quad_sums(const typename Layout::Raw& raw, i
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         key[j] = Layout::key(raw, j);
-        w[j] = *reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(pstar) + key[j]);
+        w[j] = lds_float_at((uint32_t)key[j]);
     }
     double acc = base;
 #pragma unroll
