@@ -20,7 +20,7 @@
 //     entries, loaded four at a time, accumulates them in fp64 in registers, and a DPP scan
 //     over the group gives the prefix over lanes.  The lane whose range holds the draw finds
 //     "the smallest k whose prefix exceeds it" (Section 6.1.1) among its own entries.  Rows
-//     of more than 512 entries are walked twice by a whole wave.  Token parameters and
+//     of more than 768 entries are walked twice by a whole wave.  Token parameters and
 //     results travel between the per-lane and per-group phases through small per-wave LDS
 //     records;
 //   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
@@ -57,7 +57,7 @@ struct SampleArgs {
 
 constexpr int kRowHeader = 16;  // bytes before a theta row's entries
 constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
-constexpr int kKeptQuads = 2;   // quads (of four entries) a lane keeps in registers at most
+constexpr int kKeptQuads = 3;   // quads (of four entries) a lane keeps in registers at most
 
 // Once a token's pass has read its record, the record takes the result back to the per-lane
 // phase: the new topic (or -1 for "dense bucket") in `off`, the dense draw position in `u`.
@@ -326,7 +326,7 @@ __device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, const typen
     row_store(rec, sl, d, Layout::template topic_of<kQuads>(raw, sel));
 }
 
-// Rows of more than 512 entries, one per wave (sub-lane = lane): one walk for the sums, a
+// Rows of more than 768 entries, one per wave (sub-lane = lane): one walk for the sums, a
 // second one over the hit lane's entries.  Lane l owns the entries [4 n4 l, 4 n4 (l + 1)).
 template <class Layout>
 __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenRec* rec, int K,
@@ -367,9 +367,9 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenR
 }
 
 template <int kWaves, class Layout>
-// Six waves per SIMD (80 VGPRs): the walk hides HBM latency by occupancy as well as by the
-// one-pass-ahead loads; measured faster than five waves with no spills.
-__attribute__((amdgpu_waves_per_eu(6)))
+// Five waves per SIMD (96 VGPRs): three kept quads per lane and the next pass's loads need
+// the registers; the walk hides HBM latency by occupancy as well as by those early loads.
+__attribute__((amdgpu_waves_per_eu(5)))
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int K = a.K, Kpad = a.Kpad, ng = Kpad / kGroup;
@@ -445,38 +445,45 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // tokens, as many as lets every lane own at most kKeptQuads quads; the rows of the
         // following pass are requested from memory before this one is worked on.
         const int n_here = min(kWave, tl.count - b * kWave);
-        // which tokens of the batch have rows beyond 16 .. 512 entries (lanes past the batch's
-        // end hold nnz = 0): the shape of every pass follows from these masks
-        static_assert(kKeptQuads == 2, "the pass shapes assume two kept quads per lane");
+        // Shapes of a pass (lanes per token, quads per lane -> entries per row at most):
+        //   0 (4,1) 16   1 (4,2) 32   2 (8,2) 64   3 (8,3) 96   4 (16,2) 128   5 (16,3) 192
+        //   6 (32,3) 384   7 (64,3) 768   8 = one longer row, walked twice by the wave
+        // Which tokens of the batch have rows beyond each of these lengths (lanes past the
+        // batch's end hold nnz = 0): the shape of every pass follows from these masks.
+        static_assert(kKeptQuads == 3, "the pass shapes assume three kept quads per lane");
         const uint64_t over16 = __ballot(mine.nnz > 16), over32 = __ballot(mine.nnz > 32);
-        const uint64_t over64 = __ballot(mine.nnz > 64), over128 = __ballot(mine.nnz > 128);
-        const uint64_t over256 = __ballot(mine.nnz > 256), over512 = __ballot(mine.nnz > 512);
-        // shape of the pass that starts at token t0: 0 = 4 lanes per token and one quad per
-        // lane, 1 .. 5 = 4, 8, 16, 32, 64 lanes and two quads, 6 = a row for the long walk
-        auto shape_at = [&](int t0) {
-            if (((over32 >> t0) & 0xffffull) == 0) return ((over16 >> t0) & 0xffffull) == 0 ? 0 : 1;
-            if (((over64 >> t0) & 0xffull) == 0) return 2;
-            if (((over128 >> t0) & 0xfull) == 0) return 3;
-            if (((over256 >> t0) & 0x3ull) == 0) return 4;
-            return ((over512 >> t0) & 0x1ull) == 0 ? 5 : 6;
+        const uint64_t over64 = __ballot(mine.nnz > 64), over96 = __ballot(mine.nnz > 96);
+        const uint64_t over128 = __ballot(mine.nnz > 128), over192 = __ballot(mine.nnz > 192);
+        const uint64_t over384 = __ballot(mine.nnz > 384), over768 = __ballot(mine.nnz > 768);
+        auto any = [](uint64_t mask, int t0, uint32_t window) {      // 1 if a token of the window is set
+            const uint32_t w = (uint32_t)(mask >> t0) & window;
+            return (int)((w | (0u - w)) >> 31);
         };
-        auto lanes_log2 = [](int shape) { return shape <= 1 ? 2 : shape >= 5 ? 6 : shape + 1; };
+        auto shape_at = [&](int t0) {
+            if (!any(over32, t0, 0xffffu)) return any(over16, t0, 0xffffu);
+            if (!any(over96, t0, 0xffu)) return 2 + any(over64, t0, 0xffu);
+            if (!any(over192, t0, 0xfu)) return 4 + any(over128, t0, 0xfu);
+            if (!any(over384, t0, 0x3u)) return 6;
+            return 7 + any(over768, t0, 0x1u);
+        };
+        auto lanes_log2 = [](int shape) { return (int)((0x665443322ull >> (4 * shape)) & 0xfull); };
+        auto quads_of = [](int shape) { return (int)((0x033323221ull >> (4 * shape)) & 0xfull); };
         // where a pass's rows are, and the loads of the quads its lanes keep.  `rec` is the
         // record of the lane's token, `sl` the lane's place inside its group.  A pass that
         // would run past the batch's 64 records works on the last one several times over.
         using Raw = typename Layout::Raw;
         auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, Raw* raw) {
-            const int lg = lanes_log2(shape);
+            const int lg = lanes_log2(shape), nq = quads_of(shape);
             const int g = lg < 4 ? 4 - lg : 0, hs = lg < 4 ? 4 : lg;    // interleave, run length
             const int rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
             sl = (lane & ((1 << hs) - 1)) >> g;
             rec = my_rec + min(t0 + rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             const int nnz = (int)where.y;
-            const int e0 = shape == 0 ? sl * 4 : sl * 8;
-            raw[0] = Layout::load(a.slots, where.x, nnz, e0, shape != 6 && e0 < nnz, K);
-            raw[1] = Layout::load(a.slots, where.x, nnz, e0 + 4,
-                                  shape != 6 && shape != 0 && e0 + 4 < nnz, K);
+            const int e0 = sl * (4 * nq);
+#pragma unroll
+            for (int c = 0; c < kKeptQuads; ++c)
+                raw[c] = Layout::load(a.slots, where.x, nnz, e0 + 4 * c, c < nq && e0 + 4 * c < nnz, K);
         };
         int t_next = 0, shape_next = shape_at(0), sl_next;
         TokenRec* rec_next;
@@ -494,9 +501,11 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             case 0: row_pass_kept<Layout, 4, 1>(rec, sl, mine_raw, pstar, lane); break;
             case 1: row_pass_kept<Layout, 4, 2>(rec, sl, mine_raw, pstar, lane); break;
             case 2: row_pass_kept<Layout, 8, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 3: row_pass_kept<Layout, 16, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 4: row_pass_kept<Layout, 32, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 5: row_pass_kept<Layout, 64, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 3: row_pass_kept<Layout, 8, 3>(rec, sl, mine_raw, pstar, lane); break;
+            case 4: row_pass_kept<Layout, 16, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 5: row_pass_kept<Layout, 16, 3>(rec, sl, mine_raw, pstar, lane); break;
+            case 6: row_pass_kept<Layout, 32, 3>(rec, sl, mine_raw, pstar, lane); break;
+            case 7: row_pass_kept<Layout, 64, 3>(rec, sl, mine_raw, pstar, lane); break;
             default: row_pass_long<Layout>(a.slots, rec, K, pstar, lane); break;
             }
         };
