@@ -6,11 +6,11 @@
 // bound by VALU issue, not by HBM):
 //   - a workgroup owns one tile = up to 1024 (4096 for large K) consecutive tokens of ONE
 //     word and stages that word's p*(k) (Eq. 8) once in LDS as fp32, with fp64 prefix sums
-//     over groups of 16 topics (Section 6.1.2: samplers of a block share the word's data);
+//     over groups of 4 (or 16) topics (Section 6.1.2: samplers of a block share the word's data);
 //   - each wave takes 64 tokens at a time.  What is per token and needs no cooperation is
 //     done one token per LANE: the Philox uniform, the token's own-count correction of
 //     p*(o), and the search in the dense bucket p2 (binary search over the group prefixes,
-//     then at most 16 steps);
+//     then the group's four topics);
 //   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
 //     by a GROUP of 4, 8, 16, 32 or 64 lanes per token, chosen per pass from the row lengths
 //     so that a lane owns at most eight entries (16, 8, 4, 2 or 1 tokens per pass: the fixed
@@ -49,14 +49,16 @@ struct SampleArgs {
     const unsigned char* slots;
     const int32_t* n_wk;        // [V][K]
     const int32_t* n_k;         // [K]
-    int32_t K, Kpad;            // Kpad = K+1 rounded up to 16: p*(K..Kpad-1) = 0
+    int32_t K, Kpad;            // Kpad = K+1 rounded up to a multiple of the dense group: p*(K..Kpad-1) = 0
     double alpha, beta, beta_V;
     uint64_t seed;
     uint32_t iter;
 };
 
 constexpr int kRowHeader = 16;  // bytes before a theta row's entries
-constexpr int kGroup = 16;      // topics per fp64 prefix group of the dense bucket
+// Topics per fp64 prefix group of the dense bucket: 4 where LDS has room (workgroups of four
+// waves, K <= 2048), 16 for the large-K workgroups of sixteen waves.
+__host__ __device__ constexpr int dense_group(int waves) { return waves == 4 ? 4 : 16; }
 constexpr int kKeptQuads = 3;   // quads (of four entries) a lane keeps in registers at most
 
 // Once a token's pass has read its record, the record takes the result back to the per-lane
@@ -72,13 +74,14 @@ struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
 
 // LDS bytes of sample_kernel<kWaves> for a given Kpad.
 __host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
-    return (size_t)Kpad * 4 + (size_t)((Kpad / kGroup + 1) & ~1) * 8 +
+    return (size_t)Kpad * 4 + (size_t)((Kpad / dense_group(waves) + 1) & ~1) * 8 +
            (size_t)waves * kWave * sizeof(TokenRec);
 }
 
 // Dense bucket (p2 = alpha p*', Eq. 6): smallest k with alpha * prefix'(k) > y, where
 // prefix' is the prefix sum of p* with the entry of the token's own topic o replaced by
 // w_o (delta = w_o - p*(o)).  One lane per token.
+template <int kGroup>
 __device__ __forceinline__ int dense_bucket_search(const float* pstar, const double* cp, int K,
                                                    int ng, double alpha, double y, int o,
                                                    float w_o, double delta) {
@@ -90,7 +93,20 @@ __device__ __forceinline__ int dense_bucket_search(const float* pstar, const dou
     }
     if (lo >= ng) return K - 1;
     const int k0 = lo * kGroup;
-    double acc = (lo > 0 ? cp[lo - 1] : 0.0) + (k0 > o ? delta : 0.0);
+    const double before = (lo > 0 ? cp[lo - 1] : 0.0) + (k0 > o ? delta : 0.0);
+    if (kGroup == 4) {
+        // the four topics of group `lo`, taken in one read (p* beyond K is 0 and adds nothing)
+        const float4 w = *reinterpret_cast<const float4*>(pstar + k0);
+        const double a0 = before + (double)(k0 == o ? w_o : w.x);
+        const double a1 = a0 + (double)(k0 + 1 == o ? w_o : w.y);
+        const double a2 = a1 + (double)(k0 + 2 == o ? w_o : w.z);
+        int found = k0 + 3;
+        if (alpha * a2 > y) found = k0 + 2;
+        if (alpha * a1 > y) found = k0 + 1;
+        if (alpha * a0 > y) found = k0;
+        return min(found, K - 1);
+    }
+    double acc = before;
     int found = min(k0 + kGroup - 1, K - 1);
     for (int j = 0; j < kGroup; ++j) {
         const int k = k0 + j;
@@ -193,13 +209,14 @@ struct PackedRows {
     struct Raw {
         uint4 e;
     };
+    // Every lane loads: a lane without entries reads the four padding entries that the
+    // library keeps in the first 16 bytes of the slot buffer (no slot starts there).
     static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int,
-                                               int e, bool on, int K) {
+                                               int e, bool on, int) {
+        static_assert(kRowHeader == 16, "a row's entries start one 16-byte unit into its slot");
+        const uint32_t unit = on ? off + 1u + ((uint32_t)e >> 2) : 0u;
         Raw q;
-        q.e = make_uint4((uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2);
-        if (on)
-            q.e = *reinterpret_cast<const uint4*>(
-                reinterpret_cast<const uint32_t*>(slots + (size_t)off * 16u + kRowHeader) + e);
+        q.e = *reinterpret_cast<const uint4*>(slots + (size_t)unit * 16u);
         return q;
     }
     static __device__ __forceinline__ uint32_t entry(const Raw& q, int j) {
@@ -372,6 +389,7 @@ template <int kWaves, class Layout>
 __attribute__((amdgpu_waves_per_eu(5)))
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int kGroup = dense_group(kWaves);
     const int K = a.K, Kpad = a.Kpad, ng = Kpad / kGroup;
     float* pstar = reinterpret_cast<float*>(lds);
     double* cp = reinterpret_cast<double*>(lds + (size_t)Kpad * 4);
@@ -523,7 +541,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         if (valid) {
             int z_new = (int)my_rec[lane].off;
             if (z_new < 0)
-                z_new = dense_bucket_search(pstar, cp, K, ng, a.alpha, my_rec[lane].u, mine.o, mine.w_o,
+                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, my_rec[lane].u, mine.o, mine.w_o,
                                             delta);
             a.z_next[pos] = (uint16_t)z_new;
         }

@@ -105,7 +105,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
 
 Layout layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
     const size_t tile = (size_t)tile_tokens_for(K);
-    const size_t slots = (size_t)T * 6 + (size_t)D * (mlda::kRowHeader + 18 + kSlotAlign);
+    const size_t slots = kSlotAlign + (size_t)T * 6 + (size_t)D * (mlda::kRowHeader + 18 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
     const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
     return layout_for(D, T, V, K, slots, n_tiles, n_segs, (size_t)V);
@@ -291,7 +291,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     HIP_TRY(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
     // one zero entry of p* past the last topic: padding entries of theta rows point at it
-    const int32_t Kpad = (K + mlda::kGroup) / mlda::kGroup * mlda::kGroup;
+    const int32_t dense_group = mlda::dense_group(sample_waves_for(K));
+    const int32_t Kpad = (K + dense_group) / dense_group * dense_group;
     const size_t sample_lds = mlda::sample_lds_bytes(Kpad, sample_waves_for(K));
     if (sample_lds > (size_t)lds_limit)
         return fail(MLDA_ENOTSUP, "K = " + std::to_string(K) + " needs " + std::to_string(sample_lds) +
@@ -375,6 +376,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         // ---- theta row slots: fixed capacity min(N_d, K), so rows never move; laid out in the
         // order the documents are worked on, so that rows in use together are neighbours
         row_rec.resize((size_t)D);
+        slots_bytes = kSlotAlign;       // the buffer starts with four padding entries
         for (int64_t i = 0; i < D; ++i) {
             const int64_t d = doc_order[(size_t)i];
             const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
@@ -492,6 +494,9 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
     if (e == hipSuccess) e = up(c->doc_order, doc_recs.data(), (size_t)D * sizeof(mlda::DocRec));
     if (e == hipSuccess) e = up(c->row_rec, row_rec.data(), (size_t)D * 8);
+    // what a lane of the sampler reads when it has no entries of its own (count 0, topic K)
+    const uint32_t pad_entries[4] = {(uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2};
+    if (e == hipSuccess) e = up(c->slots, pad_entries, sizeof(pad_entries));
     if (e == hipSuccess) e = up(c->tiles, tiles.data(), tiles.size() * sizeof(mlda::Tile));
     if (e == hipSuccess) e = up(c->segs, segs.data(), segs.size() * sizeof(mlda::Tile));
     if (e == hipSuccess) e = up(c->split_words, split_words.data(), split_words.size() * 4);
