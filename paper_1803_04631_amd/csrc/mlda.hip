@@ -454,7 +454,9 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->packed = packed;
     {
         const size_t theta_lds = mlda::theta_lds_bytes(K, packed);
-        const int per_cu = std::max(1, std::min(24, (int)(144 * 1024 / theta_lds)));
+        // 16 one-wave workgroups per CU: enough to hide the gathers' latency; more of them
+        // touch more lines of z at once than an XCD's L2 holds, and neighbours stop sharing
+        const int per_cu = std::max(1, std::min(16, (int)(144 * 1024 / theta_lds)));
         c->theta_grid = (int32_t)std::min<int64_t>({D, (int64_t)n_cus * per_cu, (int64_t)kMaxThetaGrid});
     }
     c->n_segs = (int32_t)segs.size();
