@@ -84,22 +84,11 @@ __device__ __forceinline__ void block_partial_store(double v, double* partial) {
     }
 }
 
-// lgG(c + a) - lgG(a) for the small integer counts that make up almost all cells, from a
-// table each workgroup fills in LDS; larger counts call lgamma directly.
+// lgG(c + a) - lgG(a) for the small integer counts c < kLgTable that make up almost all
+// cells comes from a table, filled once per context in global memory (kLgTable entries, then
+// lgG(a) itself): the kernels that use it call no lgamma and stay register-lean.
 constexpr int kLgTable = 1024;
 
-__device__ __forceinline__ void fill_lg_table(double* table, double a, double lg_a) {
-    for (int c = (int)threadIdx.x; c < kLgTable; c += (int)blockDim.x)
-        table[c] = lgamma((double)c + a) - lg_a;
-    __syncthreads();
-}
-
-__device__ __forceinline__ double lg_rise(const double* table, int c, double a, double lg_a) {
-    return c < kLgTable ? table[c] : lgamma((double)c + a) - lg_a;
-}
-
-// The same table in global memory (kLgTable entries, then lgG(a) itself), filled once per
-// context: lets a register-lean kernel avoid lgamma altogether.
 __global__ void lg_table_kernel(double* table, double a) {
     const double lg_a = lgamma(a);
     const int c = (int)(blockIdx.x * blockDim.x + threadIdx.x);
@@ -317,20 +306,35 @@ __global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_i
 
 // ------------------------------------------------------------------ log-likelihood kernels
 
+// Word side: sum over all cells of lgG(n_wk + beta) - lgG(beta), plus the topic totals' term.
+// Cells are read four at a time; the table of small counts comes ready-made from global
+// memory (lg_table: kLgTable entries, then lgG(beta)), larger counts use Stirling's series.
 __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_wk, int64_t n_cells,
                                                                const int32_t* n_k, int32_t K,
                                                                double beta, double v_beta,
+                                                               const double* lg_table,
                                                                double* partial) {
     __shared__ double table[kLgTable];
-    const double lg_beta = lgamma(beta);
-    fill_lg_table(table, beta, lg_beta);
+    for (int c = (int)threadIdx.x; c < kLgTable; c += 256) table[c] = lg_table[c];
+    const double lg_beta = lg_table[kLgTable];
+    __syncthreads();
     double acc = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_cells; i += stride) {
-        const int c = n_wk[i];
-        if (c > 0) acc += lg_rise(table, c, beta, lg_beta);
+    auto add_cell = [&](int c) {
+        if (c > 0 && c < kLgTable) acc += table[c];
+        if (__ballot(c >= kLgTable) != 0) {          // rare: taken by the whole wave or not at all
+            if (c >= kLgTable) acc += lgamma_large((double)c + beta) - lg_beta;
+        }
+    };
+    const int64_t n_quads = n_cells / 4, stride = (int64_t)gridDim.x * blockDim.x;
+    const int4* quads = reinterpret_cast<const int4*>(n_wk);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_quads; i += stride) {
+        const int4 v = quads[i];
+        if (__ballot((v.x | v.y | v.z | v.w) != 0) == 0) continue;
+        add_cell(v.x); add_cell(v.y); add_cell(v.z); add_cell(v.w);
     }
     if (blockIdx.x == 0) {
+        const int64_t i = 4 * n_quads + (int64_t)threadIdx.x;      // up to three cells are left
+        add_cell(i < n_cells ? n_wk[i] : 0);
         const double lg_vb = lgamma(v_beta);
         for (int k = (int)threadIdx.x; k < K; k += (int)blockDim.x)
             acc += lg_vb - lgamma((double)n_k[k] + v_beta);

@@ -97,7 +97,7 @@ Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes
     L.split = n_split * 4;
     L.ll_partial = (size_t)(2 * kLoglikBlocks + kMaxThetaGrid) * 8;
     L.ll_value = 8;
-    L.lg_table = (size_t)(mlda::kLgTable + 1) * 8;
+    L.lg_table = (size_t)(mlda::kLgTable + 1) * 8 * 2;     // one for alpha, one for beta
     L.row_entries = (size_t)kEntryRing * 8;
     L.finish();
     return L;
@@ -146,6 +146,7 @@ struct mlda_ctx {
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
     double *ll_partial = nullptr, *ll_value = nullptr;
     double* lg_table = nullptr;          // lgG(c + alpha) - lgG(alpha), c < 1024, then lgG(alpha)
+    double* lg_table_beta = nullptr;     // the same for beta
     unsigned long long* row_entries = nullptr;   // ring: [r % kEntryRing] written by rebuild r
     int64_t rebuilds = 0;                        // rebuilds launched so far
     int32_t last_step_iters = 0;
@@ -212,7 +213,8 @@ int launch_loglik(mlda_ctx* c) {
     using namespace mlda;
     const int64_t cells = (int64_t)c->V * c->K;
     hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->n_wk,
-                       cells, c->n_k, c->K, c->beta, (double)c->V * c->beta, c->ll_partial);
+                       cells, c->n_k, c->K, c->beta, (double)c->V * c->beta, c->lg_table_beta,
+                       c->ll_partial);
     hipLaunchKernelGGL(loglik_doc_term_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
                        c->doc_ptr, c->D, (double)c->K * c->alpha, c->ll_partial + kLoglikBlocks);
     hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial,
@@ -483,6 +485,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->ll_partial = (double*)take(L.ll_partial);
     c->ll_value = (double*)take(L.ll_value);
     c->lg_table = (double*)take(L.lg_table);
+    c->lg_table_beta = c->lg_table + (mlda::kLgTable + 1);
     c->row_entries = (unsigned long long*)take(L.row_entries);
 
     auto up = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
@@ -505,6 +508,8 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     if (e == hipSuccess) {
         hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
                            c->stream, c->lg_table, alpha);
+        hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
+                           c->stream, c->lg_table_beta, beta);
         // rows of words without tokens are never written again: start phi at zero
         const int64_t cells = (int64_t)V * K;
         hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
