@@ -431,6 +431,9 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     __syncthreads();
     const double W = cp[ng - 1];           // sum_k p*(k);  Q = alpha W (Eq. 7)
 
+    // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
+    // place inside its group, its first entry
+    int geo_shape = -1, geo_rel = 0, geo_sl = 0, geo_e0 = 0;
     const int n_batches = (tl.count + kWave - 1) / kWave;
     for (int b = wave; b < n_batches; b += kWaves) {
         // ---- one token per lane: token, uniform, own-count correction
@@ -491,14 +494,20 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // would run past the batch's 64 records works on the last one several times over.
         using Raw = typename Layout::Raw;
         auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, Raw* raw) {
-            const int lg = lanes_log2(shape), nq = quads_of(shape);
-            const int g = lg < 4 ? 4 - lg : 0, hs = lg < 4 ? 4 : lg;    // interleave, run length
-            const int rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
-            sl = (lane & ((1 << hs) - 1)) >> g;
-            rec = my_rec + min(t0 + rel, kWave - 1);
+            const int nq = quads_of(shape);
+            if (shape != geo_shape) {       // the lanes' places change only with the shape
+                const int lg = lanes_log2(shape);
+                const int g = lg < 4 ? 4 - lg : 0, hs = lg < 4 ? 4 : lg;    // interleave, run length
+                geo_shape = shape;
+                geo_rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
+                geo_sl = (lane & ((1 << hs) - 1)) >> g;
+                geo_e0 = geo_sl * (4 * nq);
+            }
+            sl = geo_sl;
+            rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             const int nnz = (int)where.y;
-            const int e0 = sl * (4 * nq);
+            const int e0 = geo_e0;
 #pragma unroll
             for (int c = 0; c < kKeptQuads; ++c)
                 raw[c] = Layout::load(a.slots, where.x, nnz, e0 + 4 * c, c < nq && e0 + 4 * c < nnz, K);
