@@ -65,12 +65,19 @@ static double stream_normal(stream_t* g) {
     return sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
 }
 
-static int64_t stream_poisson(stream_t* g, double lambda) {
-    /* product-of-uniforms method; lambda is at most a few hundred here */
+static int64_t stream_poisson_small(stream_t* g, double lambda) {
+    /* product-of-uniforms method; exp(-lambda) must stay a normal number */
     double limit = exp(-lambda), p = 1.0;
     int64_t n = -1;
     do { p *= stream_u01(g); ++n; } while (p > limit);
     return n;
+}
+
+static int64_t stream_poisson(stream_t* g, double lambda) {
+    /* a Poisson variate of large mean is the sum of independent ones of small means */
+    int64_t n = 0;
+    while (lambda > 500.0) { n += stream_poisson_small(g, 500.0); lambda -= 500.0; }
+    return n + stream_poisson_small(g, lambda);
 }
 
 /*

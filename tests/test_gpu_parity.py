@@ -116,6 +116,9 @@ EDGE_CASES = [
     # documents of 2^14 tokens or more: the library falls back to 6-byte theta entries
     ("huge_docs_split_rows", 3,   400,  700, 17000),
     ("huge_docs_few_topics", 4,   50,   24,  16500),
+    # rows of more than 768 entries: walked twice by a whole wave (4-byte and 6-byte entries)
+    ("rows_over_768",        6,   300,  1200, 9000),
+    ("rows_over_768_split",  3,   300,  1100, 17500),
 ]
 
 
@@ -129,6 +132,34 @@ def test_edge_shapes(mlda, case):
     model.init_random()
     z = oracle.init_topics(c.T, K, SEED)
     assert np.array_equal(model.assignments(), z)
+    for it in (1, 2, 3):
+        z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
+    model.close()
+
+
+def test_mixed_row_lengths(mlda):
+    """Documents of 3 to ~1500 tokens over few words: every group width and quad count of the
+    row walk occurs, and the 64 tokens a wave takes together mix several of them."""
+    V, K = 24, 2000
+    parts = [corpus_synth.tiny(D=5, V=V, K=K, mean_len=m, seed=int(m), name="part")
+             for m in (3, 12, 28, 45, 75, 110, 170, 300, 600, 1000, 1500)]
+    lens = np.concatenate([np.diff(p.doc_ptr) for p in parts])
+    order = np.random.default_rng(5).permutation(len(lens))          # lengths in no order
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    words_by_doc = np.concatenate([p.word_ids for p in parts])
+    words = np.concatenate([words_by_doc[starts[d]:starts[d + 1]] for d in order]).astype(np.int32)
+    doc_ptr = np.concatenate([[0], np.cumsum(lens[order])]).astype(np.int64)
+
+    class C:  # minimal corpus record
+        pass
+    c = C(); c.doc_ptr = doc_ptr; c.word_ids = words; c.T = len(words)
+    alpha, beta = 50.0 / K, 0.01
+    say("mixed_row_lengths T", c.T, "longest", lens.max())
+    model = mlda.Mlda(doc_ptr, words, V, K, alpha, beta, SEED)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, SEED)
+    nnz = np.diff(model.doc_topic_csr()[0])
+    assert nnz.min() <= 16 and nnz.max() > 768      # from the narrowest shape to the long walk
     for it in (1, 2, 3):
         z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
     model.close()
