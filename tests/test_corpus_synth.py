@@ -47,3 +47,14 @@ def test_documents_are_topically_sparse():
     doc = np.repeat(np.arange(c.config.D), np.diff(c.doc_ptr))
     nnz = len(np.unique(doc.astype(np.int64) * c.config.K + c.z_true)) / c.config.D
     assert nnz < 0.6 * np.diff(c.doc_ptr).mean()
+
+
+def test_poisson_lengths_of_large_mean():
+    """Document lengths follow the requested mean also where exp(-mean) underflows (a
+    product-of-uniforms sampler alone would stop near 745 tokens)."""
+    for mean in (300.0, 2000.0, 17000.0):
+        c = cs.tiny(D=200, V=50, K=8, mean_len=mean, seed=11)
+        lens = np.diff(c.doc_ptr)
+        # Poisson: mean and variance both equal `mean`; 200 documents
+        assert abs(lens.mean() - mean) < 5 * np.sqrt(mean / 200)
+        assert 0.6 * mean < lens.var() < 1.5 * mean
