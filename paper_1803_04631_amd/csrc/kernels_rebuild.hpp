@@ -65,6 +65,21 @@ __global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, in
     }
 }
 
+// The same totals as column sums of n_wk (cheaper than a pass over z when V K is small next to
+// T): thread x of a workgroup owns topic blockIdx.x * 256 + x, workgroup row blockIdx.y a
+// slice of the words; reads are coalesced along a word's row.  n_k must be zero on entry.
+__global__ __launch_bounds__(256) void topic_totals_from_rows_kernel(const int32_t* n_wk, int32_t V,
+                                                                     int32_t K, int32_t words_per_slice,
+                                                                     int32_t* n_k) {
+    const int k = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (k >= K) return;
+    const int v0 = (int)blockIdx.y * words_per_slice;
+    const int v1 = min(v0 + words_per_slice, V);
+    int acc = 0;
+    for (int v = v0; v < v1; ++v) acc += n_wk[(size_t)v * (size_t)K + k];
+    if (acc != 0) atomicAdd(&n_k[k], acc);
+}
+
 // ------------------------------------------------------------------ log-likelihood helpers
 // log p(w,z) = sum_k [lgG(V beta) - lgG(n_k + V beta)] + sum_{v,k} [lgG(n_wk + beta) - lgG(beta)]
 //            + sum_d [lgG(K alpha) - lgG(N_d + K alpha)] + sum_{d,k} [lgG(n_dk + alpha) - lgG(alpha)]

@@ -184,9 +184,17 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
     if (c->n_tiles > 0) {
         hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes,
                            c->stream, c->segs, z, c->n_wk, c->K);
-        const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
-        hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes,
-                           c->stream, z, c->T, c->n_k, c->K);
+        if ((int64_t)c->V * c->K * 2 < c->T) {
+            // n_k as column sums of the fresh n_wk: fewer bytes than z and no LDS atomics
+            const int words_per_slice = 64;
+            dim3 grid((unsigned)blocks_for(c->K, 256), (unsigned)blocks_for(c->V, words_per_slice));
+            hipLaunchKernelGGL(topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream, c->n_wk,
+                               c->V, c->K, words_per_slice, c->n_k);
+        } else {
+            const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
+            hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes,
+                               c->stream, z, c->T, c->n_k, c->K);
+        }
     }
     if (ev_phi) HIP_TRY(hipEventRecord(*ev_phi, c->stream));
     if (c->D > 0) {
