@@ -33,8 +33,9 @@
  *     or written during the call.  The device workspace and the HIP stream are
  *     the caller's too (e.g. a torch uint8 CUDA tensor and
  *     torch.cuda.current_stream().cuda_stream); the library allocates no device
- *     memory, keeps the workspace until mlda_destroy, and launches all work on
- *     that stream.  Getters synchronise the stream.
+ *     memory, keeps the workspace until mlda_destroy, and launches all kernels on
+ *     that stream (a context made by mlda_create_streamed also owns pinned host
+ *     memory and a copy stream).  Getters synchronise the stream.
  *   - A context is not thread-safe.  Token order at the boundary is always the
  *     caller's document-major order; the word-major order used on the device is
  *     internal.
@@ -79,6 +80,30 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
 int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                 int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
                 void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The same with the corpus cut by document into n_chunks chunks of about equal token
+ * counts that take turns on the GPU (Section 4: partition by document; Algorithm 1,
+ * WorkSchedule2: with more than one chunk per GPU the chunks are transferred every
+ * iteration, phi stays on the device).  For corpora whose tokens and theta rows do not fit
+ * the device beside phi.  The preprocessed chunks and all assignments are kept in pinned
+ * host memory that the library allocates; per iteration every chunk is uploaded (on a second
+ * stream of default priority that the library creates, overlapping the kernels of the chunk
+ * before), its theta rows are rebuilt from its assignments, it is sampled against the phi of
+ * the iteration's start, its counts are added to the next phi, and its new assignments go
+ * back to the host.  Results are identical, bit for bit, to those of mlda_create: the counts
+ * of an iteration are frozen and the uniforms are keyed by the caller's token index.
+ * The workspace (mlda_workspace_bytes_streamed: two copies of phi and two chunk buffers) and
+ * the other arguments are as for mlda_create; doc_ptr is read by the sizing call too.
+ * Differences in use: mlda_get_timing and mlda_get_sampler_bytes report no rows; the theta
+ * getters and mlda_get_loglik (when the last step did not evaluate it) revisit every chunk.
+ */
+int mlda_workspace_bytes_streamed(const int64_t* doc_ptr, int64_t D, int32_t V, int32_t K,
+                                  int32_t n_chunks, size_t* bytes);
+int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
+                         int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                         int32_t n_chunks, void* dev_workspace, size_t workspace_bytes,
+                         void* hip_stream);
 
 /* Random initial topics (Section 2.1), z[t] = floor(u(seed, 0, t) K); rebuilds all
  * counts; the iteration counter becomes 0. */
@@ -138,7 +163,8 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
  */
 int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);
 
-/* Releases the context (host memory and events); the workspace stays the caller's. */
+/* Releases the context (host memory, events, its copy stream if any); the workspace stays
+ * the caller's. */
 void mlda_destroy(mlda_ctx* ctx);
 
 /* n uniforms of iteration iter for tokens token0 .. token0+n-1 into DEVICE memory

@@ -40,6 +40,8 @@ def load_library() -> ctypes.CDLL:
     sig = {
         "mlda_workspace_bytes": [i64, i64, i32, i32, p],
         "mlda_create": [p, p, p, i64, i32, i32, dbl, dbl, u64, p, sz, p],
+        "mlda_workspace_bytes_streamed": [p, i64, i32, i32, i32, p],
+        "mlda_create_streamed": [p, p, p, i64, i32, i32, dbl, dbl, u64, i32, p, sz, p],
         "mlda_init_random": [p],
         "mlda_set_assignments": [p, p, i32],
         "mlda_step": [p, i32, u32],
@@ -68,7 +70,8 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
-EXPORTED = ["mlda_workspace_bytes", "mlda_create", "mlda_init_random", "mlda_set_assignments",
+EXPORTED = ["mlda_workspace_bytes", "mlda_create", "mlda_workspace_bytes_streamed",
+            "mlda_create_streamed", "mlda_init_random", "mlda_set_assignments",
             "mlda_step", "mlda_iteration", "mlda_get_assignments", "mlda_get_word_topic",
             "mlda_get_topic_totals", "mlda_get_doc_topic_nnz", "mlda_get_doc_topic_csr",
             "mlda_get_loglik", "mlda_get_timing", "mlda_get_sampler_bytes", "mlda_destroy",
@@ -97,10 +100,12 @@ def philox_uniform(seed: int, it: int, token0: int, n: int):
 
 
 class Mlda:
-    """One corpus resident on the GPU (Algorithm 1, WorkSchedule1 with a single chunk)."""
+    """One corpus on the GPU: resident (Algorithm 1, WorkSchedule1 with a single chunk), or with
+    chunks > 1 cut by document into that many chunks that are streamed through the GPU every
+    iteration (WorkSchedule2)."""
 
     def __init__(self, doc_ptr, word_ids, V: int, K: int, alpha: float, beta: float, seed: int,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", chunks: int = 1):
         import torch
         self._lib = load_library()
         if not torch.cuda.is_available():
@@ -111,15 +116,28 @@ class Mlda:
         self.D, self.T, self.V, self.K = len(self.doc_ptr) - 1, len(word_ids), int(V), int(K)
         self.alpha, self.beta, self.seed = float(alpha), float(beta), int(seed)
         self.device = torch.device(device)
+        self.chunks = int(chunks)
         with torch.cuda.device(self.device):
-            need = workspace_bytes(self.D, self.T, self.V, self.K)
-            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
             self.stream = torch.cuda.current_stream(self.device)
             ctx = ctypes.c_void_p()
-            _check(self._lib.mlda_create(ctypes.addressof(ctx), self.doc_ptr.ctypes.data,
-                                         word_ids.ctypes.data, self.D, self.V, self.K, self.alpha,
-                                         self.beta, self.seed, self.workspace.data_ptr(), need,
-                                         self.stream.cuda_stream))
+            if self.chunks == 1:
+                need = workspace_bytes(self.D, self.T, self.V, self.K)
+                self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+                _check(self._lib.mlda_create(ctypes.addressof(ctx), self.doc_ptr.ctypes.data,
+                                             word_ids.ctypes.data, self.D, self.V, self.K, self.alpha,
+                                             self.beta, self.seed, self.workspace.data_ptr(), need,
+                                             self.stream.cuda_stream))
+            else:
+                n = ctypes.c_size_t()
+                _check(self._lib.mlda_workspace_bytes_streamed(self.doc_ptr.ctypes.data, self.D, self.V,
+                                                               self.K, self.chunks, ctypes.addressof(n)))
+                need = n.value
+                self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+                _check(self._lib.mlda_create_streamed(ctypes.addressof(ctx), self.doc_ptr.ctypes.data,
+                                                      word_ids.ctypes.data, self.D, self.V, self.K,
+                                                      self.alpha, self.beta, self.seed, self.chunks,
+                                                      self.workspace.data_ptr(), need,
+                                                      self.stream.cuda_stream))
         self._ctx = ctx
 
     # -- state

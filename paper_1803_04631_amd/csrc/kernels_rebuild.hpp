@@ -313,10 +313,12 @@ __global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_m
     if (t < T) z_doc[t] = z_word[doc_map[t]];
 }
 
+// (tok_id counts from the start of the whole corpus, z_doc from token `first`: a chunk of
+// documents holds the tokens first .. first + T - 1.)
 __global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_id,
-                                     uint16_t* z_word, int64_t T) {
+                                     uint16_t* z_word, int64_t T, int64_t first) {
     const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pos < T) z_word[pos] = z_doc[tok_id[pos]];
+    if (pos < T) z_word[pos] = z_doc[(int64_t)tok_id[pos] - first];
 }
 
 // ------------------------------------------------------------------ log-likelihood kernels
@@ -369,11 +371,18 @@ __global__ __launch_bounds__(256) void loglik_doc_term_kernel(const int32_t* doc
     block_partial_store(acc, partial);
 }
 
+// out = (add_to_out ? *out : 0) + sum of the n partials + *extra (if given).  One workgroup,
+// fixed order.
 __global__ __launch_bounds__(256) void loglik_final_kernel(const double* partial, int n,
+                                                           const double* extra, int add_to_out,
                                                            double* out) {
     __shared__ double buf[256];
     double acc = 0.0;
     for (int i = (int)threadIdx.x; i < n; i += 256) acc += partial[i];
+    if (threadIdx.x == 0) {
+        if (extra) acc += *extra;
+        if (add_to_out) acc += *out;
+    }
     buf[threadIdx.x] = acc;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {

@@ -1,10 +1,14 @@
 // libmlda.so: C ABI, context and host-side preprocessing (see include/mlda.h).
 //
 // Paper sections behind the host steps: Section 6.1.2 (tokens are sorted word-first and
-// the tokens of heavy words are split over several workgroups that are issued first),
-// Section 6.2 (a document->token map built on the CPU lets the theta update find a
-// document's tokens in the word-sorted arrays), Algorithm 1 WorkSchedule1 with one
-// chunk on one GPU (transfer once, then iterate on the device).
+// the tokens of heavy words are split over several workgroups), Section 6.2 (a
+// document->token map built on the CPU lets the theta update find a document's tokens in
+// the word-sorted arrays), Section 4 and Algorithm 1 (the corpus is partitioned by document
+// into chunks; WorkSchedule1: one chunk, transferred once, iterated on the device;
+// WorkSchedule2: several chunks per GPU, transferred every iteration while phi stays).
+//
+// A context is the model (phi, n_k, tables) plus the chunk that is attached at the moment:
+// with one chunk it is attached once and for all, with several each is attached in turn.
 #include "../../include/mlda.h"
 
 #include <hip/hip_runtime.h>
@@ -37,6 +41,12 @@ int fail(int code, const std::string& msg) {
             return fail(MLDA_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
     } while (0)
 
+#define RC_TRY(expr)                   \
+    do {                               \
+        const int rc_ = (expr);        \
+        if (rc_ != MLDA_OK) return rc_; \
+    } while (0)
+
 constexpr size_t kAlign = 256;        // workspace sub-buffer alignment
 constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
 // waves per sampling workgroup: more of them share one staged p* column when K is large
@@ -62,53 +72,69 @@ size_t slot_bytes_for(int64_t cap, int entry_bytes) {   // cap = largest nnz the
                     kSlotAlign);
 }
 
-// Sizes of every workspace sub-buffer, as upper bounds from (D, T, V, K) or exactly.
-struct Layout {
-    size_t tok_slot, tok_id, doc_map, z0, z1, doc_ptr, doc_order, row_rec, slots, n_wk, n_k, tiles, segs, split,
-        ll_partial, ll_value, lg_table, row_entries, total;
-    void finish() {
-        size_t* parts[] = {&tok_slot, &tok_id, &doc_map, &z0, &z1, &doc_ptr, &doc_order, &row_rec, &slots,
-                           &n_wk, &n_k, &tiles, &segs, &split, &ll_partial, &ll_value, &lg_table, &row_entries};
-        total = 0;
-        for (size_t* p : parts) { *p = align_up(*p, kAlign); total += *p; }
-    }
-};
-
 constexpr int kLoglikBlocks = 2048;
 constexpr int kMaxThetaGrid = 8192;    // workgroups of the theta rebuild (each leaves one likelihood partial)
 constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entries (> kMaxTimedIters)
 
-Layout layout_for(int64_t D, int64_t T, int32_t V, int32_t K, size_t slots_bytes, size_t n_tiles,
-                  size_t n_segs, size_t n_split) {
-    Layout L{};
-    L.tok_slot = (size_t)T * 4;
-    L.tok_id = (size_t)T * 4;
-    L.doc_map = (size_t)T * 4;
-    L.z0 = (size_t)T * 2;
-    L.z1 = (size_t)T * 2;
-    L.doc_ptr = (size_t)(D + 1) * 4;
-    L.doc_order = (size_t)D * sizeof(mlda::DocRec);
-    L.row_rec = (size_t)D * 8;
-    L.slots = slots_bytes;
-    L.n_wk = (size_t)V * (size_t)K * 4;
-    L.n_k = (size_t)K * 4;
-    L.tiles = n_tiles * sizeof(mlda::Tile);
-    L.segs = n_segs * sizeof(mlda::Tile);
-    L.split = n_split * 4;
-    L.ll_partial = (size_t)(2 * kLoglikBlocks + kMaxThetaGrid) * 8;
-    L.ll_value = 8;
-    L.lg_table = (size_t)(mlda::kLgTable + 1) * 8 * 2;     // one for alpha, one for beta
-    L.row_entries = (size_t)kEntryRing * 8;
-    L.finish();
+// Where the buffers of one chunk of documents lie inside its part of the workspace (byte
+// offsets).  The static part (up to static_bytes) is the preprocessed corpus and is copied
+// from the host as one block; z and the theta rows follow.
+struct ChunkLayout {
+    size_t tok_slot = 0, tok_id = 0, doc_map = 0, doc_ptr = 0, doc_order = 0, row_rec = 0, tiles = 0,
+           segs = 0, split = 0, static_bytes = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
+};
+
+ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tiles, size_t n_segs,
+                         size_t n_split) {
+    ChunkLayout L;
+    size_t at = 0;
+    auto put = [&](size_t bytes) { const size_t o = at; at += align_up(bytes, kAlign); return o; };
+    L.tok_slot = put((size_t)T * 4);
+    L.tok_id = put((size_t)T * 4);
+    L.doc_map = put((size_t)T * 4);
+    L.doc_ptr = put((size_t)(D + 1) * 4);
+    L.doc_order = put((size_t)D * sizeof(mlda::DocRec));
+    L.row_rec = put((size_t)D * 8);
+    L.tiles = put(n_tiles * sizeof(mlda::Tile));
+    L.segs = put(n_segs * sizeof(mlda::Tile));
+    L.split = put(n_split * 4);
+    L.static_bytes = at;
+    L.z0 = put((size_t)T * 2);
+    L.z1 = put((size_t)T * 2);
+    L.slots = put(slots_bytes);
+    L.total = at;
     return L;
 }
 
-Layout layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
+// An upper bound of the same from the sizes alone.
+ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
     const size_t tile = (size_t)tile_tokens_for(K);
     const size_t slots = kSlotAlign + (size_t)T * 6 + (size_t)D * (mlda::kRowHeader + 18 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
     const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
-    return layout_for(D, T, V, K, slots, n_tiles, n_segs, (size_t)V);
+    return chunk_layout(D, T, slots, n_tiles, n_segs, (size_t)V);
+}
+
+// The model and the scratch of the reductions.
+struct ModelLayout {
+    size_t n_wk[2] = {0, 0}, n_k[2] = {0, 0}, ll_partial = 0, ll_scalars = 0, lg_table = 0, row_entries = 0,
+           total = 0;
+};
+
+ModelLayout model_layout(int32_t V, int32_t K, bool two_phi) {
+    ModelLayout L;
+    size_t at = 0;
+    auto put = [&](size_t bytes) { const size_t o = at; at += align_up(bytes, kAlign); return o; };
+    L.n_wk[0] = put((size_t)V * (size_t)K * 4);
+    L.n_wk[1] = two_phi ? put((size_t)V * (size_t)K * 4) : L.n_wk[0];
+    L.n_k[0] = put((size_t)K * 4);
+    L.n_k[1] = two_phi ? put((size_t)K * 4) : L.n_k[0];
+    L.ll_partial = put((size_t)(2 * kLoglikBlocks + kMaxThetaGrid) * 8);
+    L.ll_scalars = put(4 * 8);                            // value, theta sum, document term, spare
+    L.lg_table = put((size_t)(mlda::kLgTable + 1) * 8 * 2);   // one for alpha, one for beta
+    L.row_entries = put((size_t)kEntryRing * 8);
+    L.total = at;
+    return L;
 }
 
 template <class F>
@@ -119,44 +145,263 @@ void parallel_chunks(int n_chunks, F&& body) {
     for (auto& t : pool) t.join();
 }
 
+// Documents [d_begin, d_end) of the corpus, preprocessed: the static part of the chunk's
+// buffers, laid out as on the device.
+struct HostChunk {
+    int64_t d_begin = 0, d_end = 0;
+    int64_t tok_begin = 0;              // caller's index of the chunk's first token
+    int64_t D = 0, T = 0;
+    bool packed = true;                 // theta rows as 4-byte entries (no document has 2^14 tokens)
+    size_t slots_bytes = 0;
+    int32_t n_tiles = 0, n_segs = 0, n_split = 0;
+    ChunkLayout L;
+    unsigned char* arena = nullptr;     // L.static_bytes bytes
+    bool pinned = false;
+
+    HostChunk() = default;
+    HostChunk(const HostChunk&) = delete;
+    HostChunk& operator=(const HostChunk&) = delete;
+    ~HostChunk() { release(); }
+    void release() {
+        if (arena) {
+            if (pinned) (void)hipHostFree(arena); else std::free(arena);
+            arena = nullptr;
+        }
+    }
+};
+
+// Word-first order (Section 6.1.2), document->token map (Section 6.2), theta row slots, tiles.
+// Inside a word the tokens are put in order of falling document length, so that the theta
+// rows a wave walks together have similar lengths; any order inside a word gives the same
+// result, because the uniforms are keyed by the caller's token index.  `accumulate`: the
+// chunk's counts will be added to phi (several chunks) instead of stored.
+int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64_t d_begin,
+                  int64_t d_end, int32_t V, int32_t K, bool accumulate, bool pinned, HostChunk& h) {
+    const int64_t D = d_end - d_begin;
+    const int64_t tok_begin = doc_ptr_all[d_begin];
+    const int64_t T = doc_ptr_all[d_end] - tok_begin;
+    const int32_t* word_ids = word_ids_all ? word_ids_all + tok_begin : nullptr;
+    auto len_of = [&](int64_t d) { return doc_ptr_all[d_begin + d + 1] - doc_ptr_all[d_begin + d]; };
+    auto start_of = [&](int64_t d) { return doc_ptr_all[d_begin + d] - tok_begin; };
+    h.d_begin = d_begin; h.d_end = d_end; h.tok_begin = tok_begin; h.D = D; h.T = T;
+
+    int64_t longest_doc = 0;
+    for (int64_t d = 0; d < D; ++d) longest_doc = std::max(longest_doc, len_of(d));
+    // a count never exceeds the document's length: 4-byte theta entries if 14 bits hold it
+    h.packed = longest_doc <= mlda::PackedRows::kMaxCount;
+    const int entry_bytes = h.packed ? mlda::PackedRows::kEntryBytes : mlda::SplitRows::kEntryBytes;
+
+    std::vector<int32_t> doc_order;              // documents by falling length
+    std::vector<int64_t> order_tokens;           // tokens before each position of doc_order
+    std::vector<uint32_t> slot_of;               // slot offset of each document, 16-byte units
+    std::vector<int32_t> word_ptr;
+    try {
+        doc_order.resize((size_t)D);
+        order_tokens.resize((size_t)D + 1);
+        std::vector<int64_t> len_start((size_t)longest_doc + 2, 0);
+        for (int64_t d = 0; d < D; ++d) ++len_start[(size_t)(longest_doc - len_of(d)) + 1];
+        for (int64_t l = 0; l <= longest_doc; ++l) len_start[(size_t)l + 1] += len_start[(size_t)l];
+        for (int64_t d = 0; d < D; ++d) doc_order[(size_t)len_start[(size_t)(longest_doc - len_of(d))]++] = (int32_t)d;
+        order_tokens[0] = 0;
+        for (int64_t i = 0; i < D; ++i)
+            order_tokens[(size_t)i + 1] = order_tokens[(size_t)i] + len_of(doc_order[(size_t)i]);
+        // theta row slots: fixed capacity min(N_d, K), so rows never move; laid out in the
+        // order the documents are worked on, so that rows in use together are neighbours.
+        // The buffer starts with four padding entries.
+        slot_of.resize((size_t)D);
+        h.slots_bytes = kSlotAlign;
+        for (int64_t i = 0; i < D; ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            if (h.slots_bytes / 16 > 0xffffffffull) return fail(MLDA_ENOTSUP, "theta rows need more than 64 GiB");
+            slot_of[(size_t)d] = (uint32_t)(h.slots_bytes / 16);
+            h.slots_bytes += slot_bytes_for(std::min<int64_t>(len_of(d), K), entry_bytes);
+        }
+        word_ptr.assign((size_t)V + 1, 0);
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+
+    // stable counting sort by word over parts of the length-sorted document sequence
+    const int n_parts = (int)std::max<int64_t>(
+        1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 32, T / 65536 + 1}));
+    std::vector<std::vector<int32_t>> part_hist(n_parts);
+    std::vector<int> part_bad(n_parts, 0);
+    // part p holds the documents doc_order[part_lo(p) .. part_lo(p+1)), about T/n_parts tokens
+    auto part_lo = [&](int p) -> int64_t {
+        if (p >= n_parts) return D;
+        const int64_t want = T / n_parts * p;
+        return std::lower_bound(order_tokens.begin(), order_tokens.end(), want) - order_tokens.begin();
+    };
+    try {
+        parallel_chunks(n_parts, [&](int p) {
+            auto& hist = part_hist[p];
+            hist.assign((size_t)V, 0);
+            for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
+                const int64_t d = doc_order[(size_t)i];
+                for (int64_t t = start_of(d); t < start_of(d) + len_of(d); ++t) {
+                    const int32_t w = word_ids[t];
+                    if (w < 0 || w >= V) { part_bad[p] = 1; return; }
+                    ++hist[w];
+                }
+            }
+        });
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    for (int p = 0; p < n_parts; ++p)
+        if (part_bad[p]) return fail(MLDA_EINVAL, "word id outside [0, V)");
+
+    const int32_t tile = tile_tokens_for(K);
+    size_t n_tiles = 0, n_segs = 0, n_split = 0;
+    for (int32_t v = 0; v < V; ++v) {
+        int32_t n = 0;
+        for (int p = 0; p < n_parts; ++p) {
+            const int32_t c = part_hist[p][v];
+            part_hist[p][v] = n;            // becomes the part's offset inside the word
+            n += c;
+        }
+        word_ptr[v + 1] = word_ptr[v] + n;
+        n_tiles += (size_t)((n + tile - 1) / tile);
+        n_segs += (size_t)((n + kPhiSegment - 1) / kPhiSegment);
+        if (!accumulate && n > kPhiSegment) ++n_split;
+    }
+    h.n_tiles = (int32_t)n_tiles; h.n_segs = (int32_t)n_segs; h.n_split = (int32_t)n_split;
+    h.L = chunk_layout(D, T, h.slots_bytes, n_tiles, n_segs, n_split);
+
+    h.release();
+    h.pinned = pinned;
+    if (pinned) {
+        void* p = nullptr;
+        if (hipHostMalloc(&p, std::max<size_t>(h.L.static_bytes, 1), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(MLDA_ENOMEM, "out of pinned host memory");
+        }
+        h.arena = (unsigned char*)p;
+    } else {
+        h.arena = (unsigned char*)std::malloc(std::max<size_t>(h.L.static_bytes, 1));
+        if (!h.arena) return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    uint32_t* tok_slot = (uint32_t*)(h.arena + h.L.tok_slot);
+    int32_t* tok_id = (int32_t*)(h.arena + h.L.tok_id);
+    int32_t* doc_map = (int32_t*)(h.arena + h.L.doc_map);
+    int32_t* doc_ptr32 = (int32_t*)(h.arena + h.L.doc_ptr);
+    mlda::DocRec* doc_recs = (mlda::DocRec*)(h.arena + h.L.doc_order);
+    uint2* row_rec = (uint2*)(h.arena + h.L.row_rec);
+    mlda::Tile* tiles = (mlda::Tile*)(h.arena + h.L.tiles);
+    mlda::Tile* segs = (mlda::Tile*)(h.arena + h.L.segs);
+    int32_t* split_words = (int32_t*)(h.arena + h.L.split);
+
+    parallel_chunks(n_parts, [&](int p) {
+        auto& start = part_hist[p];
+        for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            for (int64_t t = start_of(d); t < start_of(d) + len_of(d); ++t) {
+                const int32_t w = word_ids[t];
+                const int32_t pos = word_ptr[w] + start[w]++;
+                tok_id[pos] = (int32_t)(tok_begin + t);     // the caller's token index keys the uniforms
+                tok_slot[pos] = slot_of[(size_t)d];
+                doc_map[t] = pos;
+            }
+        }
+    });
+    part_hist.clear();
+
+    for (int64_t d = 0; d < D; ++d) doc_ptr32[d] = (int32_t)start_of(d);
+    doc_ptr32[D] = (int32_t)T;
+    for (int64_t d = 0; d < D; ++d) row_rec[d] = make_uint2(slot_of[(size_t)d], 0u);
+    for (int64_t i = 0; i < D; ++i) {
+        const int64_t d = doc_order[(size_t)i];
+        doc_recs[i] = mlda::DocRec{(int32_t)start_of(d), (int32_t)len_of(d), slot_of[(size_t)d], (int32_t)d};
+    }
+    // tiles and phi segments of one word each
+    size_t it = 0, is = 0, ip = 0;
+    for (int32_t v = 0; v < V; ++v) {
+        const int32_t n = word_ptr[v + 1] - word_ptr[v];
+        for (int32_t b = 0; b < n; b += tile)
+            tiles[it++] = mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), n <= tile ? 1 : 0};
+        if (!accumulate && n > kPhiSegment) split_words[ip++] = v;
+        for (int32_t b = 0; b < n; b += kPhiSegment)
+            segs[is++] = mlda::Tile{v, word_ptr[v] + b, std::min(kPhiSegment, n - b),
+                                    (!accumulate && n <= kPhiSegment) ? 1 : 0};
+    }
+    try {
+        // Sampling tiles run in the order of their first document (longest documents first;
+        // slot offsets rise in that order), not word by word: tiles of different words that
+        // are in flight together then walk the theta rows of the same documents, which are
+        // fetched from HBM once instead of once per heavy word.  (The paper issues the tiles
+        // of heavy words first, Section 6.1.2; here the long-row tiles come first, which also
+        // keeps the tail short.)
+        std::stable_sort(tiles, tiles + n_tiles, [&](const mlda::Tile& a, const mlda::Tile& b) {
+            return tok_slot[(size_t)a.begin] < tok_slot[(size_t)b.begin];
+        });
+        std::stable_sort(segs, segs + n_segs,
+                         [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    return MLDA_OK;
+}
+
+// Chunk m of M covers the documents [chunk_first(m), chunk_first(m + 1)): about T / M tokens each.
+int64_t chunk_first(const int64_t* doc_ptr, int64_t D, int32_t M, int32_t m) {
+    if (m <= 0) return 0;
+    if (m >= M) return D;
+    const int64_t want = doc_ptr[D] / M * m;
+    return std::lower_bound(doc_ptr, doc_ptr + D + 1, want) - doc_ptr;
+}
+
 }  // namespace
 
 struct mlda_ctx {
-    int64_t D = 0, T = 0;
+    // ---- the corpus as a whole and the model
+    int64_t D_all = 0, T_all = 0;
     int32_t V = 0, K = 0, Kpad = 0;
     double alpha = 0, beta = 0;
     uint64_t seed = 0;
     int32_t iter = 0;
     hipStream_t stream = nullptr;
     int n_cus = 0, lds_limit = 0;
-
-    uint32_t* tok_slot = nullptr;         // [T] slot of the theta row of each word-major token's document
-    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
-    mlda::DocRec* doc_order = nullptr;  // documents by falling length, as the theta rebuild walks them
-    int32_t theta_grid = 0;
-    bool packed = false;                // theta rows as 4-byte entries (no document has 2^14 tokens)
-    int32_t *n_wk = nullptr, *n_k = nullptr, *split_words = nullptr;
-    uint16_t* z[2] = {nullptr, nullptr};
-    int cur = 0;
-    uint2* row_rec = nullptr;
-    unsigned char* slots = nullptr;
-    size_t slots_bytes = 0;
-    mlda::Tile* tiles = nullptr;        // sampling tiles
-    mlda::Tile* segs = nullptr;         // phi rebuild segments
-    int32_t n_tiles = 0, n_segs = 0, n_split = 0;
-    double *ll_partial = nullptr, *ll_value = nullptr;
+    size_t sample_lds = 0;
+    int32_t* n_wk[2] = {nullptr, nullptr};   // [model_cur] is the current phi; two buffers when streamed
+    int32_t* n_k[2] = {nullptr, nullptr};
+    int model_cur = 0;
+    double *ll_partial = nullptr, *ll_scalars = nullptr;   // scalars: value, theta sum, document term
     double* lg_table = nullptr;          // lgG(c + alpha) - lgG(alpha), c < 1024, then lgG(alpha)
     double* lg_table_beta = nullptr;     // the same for beta
     unsigned long long* row_entries = nullptr;   // ring: [r % kEntryRing] written by rebuild r
     int64_t rebuilds = 0;                        // rebuilds launched so far
     int32_t last_step_iters = 0;
-
-    std::vector<int64_t> doc_ptr_host;
     bool has_state = false, ll_fresh = false;
-
     std::vector<hipEvent_t> events;     // 5 per timed iteration
     int32_t timed_iters = 0;            // iterations of the last step that carry events
-    size_t sample_lds = 0;
+
+    // ---- the chunks (one: attached for good; several: attached in turn, Algorithm 1 WorkSchedule2)
+    std::vector<HostChunk> chunks;
+    bool streamed = false;
+    unsigned char* slot_base[2] = {nullptr, nullptr};   // the workspace parts chunks are attached to
+    uint16_t* z_host = nullptr;          // streamed: all assignments in the caller's order (pinned)
+    hipStream_t copy_stream = nullptr;   // streamed: uploads run beside the kernels
+    hipEvent_t slot_ready[2] = {nullptr, nullptr}, slot_free[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> z_stored;    // per chunk: its assignments have reached z_host
+    int64_t visits = 0;                  // chunk visits so far (picks the slot)
+
+    // ---- the attached chunk
+    const HostChunk* at = nullptr;
+    int64_t D = 0, T = 0;
+    uint32_t* tok_slot = nullptr;        // [T] slot of the theta row of each word-major token's document
+    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    mlda::DocRec* doc_order = nullptr;   // documents by falling length, as the theta rebuild walks them
+    int32_t theta_grid = 0;
+    bool packed = false;
+    int32_t* split_words = nullptr;
+    uint16_t* z[2] = {nullptr, nullptr}; // word-major assignments
+    int cur = 0;
+    uint2* row_rec = nullptr;
+    unsigned char* slots = nullptr;
+    size_t slots_bytes = 0;
+    mlda::Tile* tiles = nullptr;         // sampling tiles
+    mlda::Tile* segs = nullptr;          // phi rebuild segments
+    int32_t n_tiles = 0, n_segs = 0, n_split = 0;
 };
 
 namespace {
@@ -169,34 +414,143 @@ int launch_check(const char* what) {
 
 int blocks_for(int64_t n, int per) { return (int)((n + per - 1) / per); }
 
-// phi, n_k and theta from the assignments in z (word-major).  ev: optional events
-// [after phi+n_k, after theta].
-int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_t* ev_theta) {
+// Point the context at chunk h in workspace part `base` (no data moves).
+void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
+    c->at = &h;
+    c->D = h.D; c->T = h.T;
+    c->packed = h.packed;
+    c->slots_bytes = h.slots_bytes;
+    c->n_tiles = h.n_tiles; c->n_segs = h.n_segs; c->n_split = h.n_split;
+    c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
+    c->tok_id = (int32_t*)(base + h.L.tok_id);
+    c->doc_map = (int32_t*)(base + h.L.doc_map);
+    c->doc_ptr = (int32_t*)(base + h.L.doc_ptr);
+    c->doc_order = (mlda::DocRec*)(base + h.L.doc_order);
+    c->row_rec = (uint2*)(base + h.L.row_rec);
+    c->tiles = (mlda::Tile*)(base + h.L.tiles);
+    c->segs = (mlda::Tile*)(base + h.L.segs);
+    c->split_words = (int32_t*)(base + h.L.split);
+    c->z[0] = (uint16_t*)(base + h.L.z0);
+    c->z[1] = (uint16_t*)(base + h.L.z1);
+    c->slots = base + h.L.slots;
+    c->cur = 0;
+    const size_t theta_lds = mlda::theta_lds_bytes(c->K, h.packed);
+    // 16 one-wave workgroups per CU: enough to hide the gathers' latency; more of them
+    // touch more lines of z at once than an XCD's L2 holds, and neighbours stop sharing
+    const int per_cu = std::max(1, std::min(16, (int)(144 * 1024 / theta_lds)));
+    c->theta_grid = (int32_t)std::min<int64_t>({h.D, (int64_t)c->n_cus * per_cu, (int64_t)kMaxThetaGrid});
+}
+
+// What a lane of the sampler reads when it has no entries of its own: four padding entries
+// (count 0, topic K) at the start of the slot buffer.
+void write_padding_entries(mlda_ctx* c) {
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(1), dim3(256), 0, c->stream, (int32_t*)c->slots,
+                       (int64_t)4, (int32_t)((uint32_t)c->K << 2));
+}
+
+// Streamed: bring chunk m into the slot of this visit.  The static part (and with_z: the
+// chunk's assignments, caller's order, into z[1]) is copied on the copy stream, so that it
+// overlaps the kernels of the chunk before; the context's stream then waits for it and, with_z,
+// turns the assignments into word-major order in z[0].
+int attach(mlda_ctx* c, int32_t m, bool with_z) {
+    const HostChunk& h = c->chunks[(size_t)m];
+    const int s = (int)(c->visits % 2);
+    c->visits += 1;
+    point_at(c, h, c->slot_base[s]);
+    // the slot's previous user must be done, and this chunk's last assignments stored
+    HIP_TRY(hipStreamWaitEvent(c->copy_stream, c->slot_free[s], 0));
+    if (h.L.static_bytes > 0)
+        HIP_TRY(hipMemcpyAsync(c->slot_base[s], h.arena, h.L.static_bytes, hipMemcpyHostToDevice,
+                               c->copy_stream));
+    if (with_z && h.T > 0) {
+        HIP_TRY(hipStreamWaitEvent(c->copy_stream, c->z_stored[(size_t)m], 0));
+        HIP_TRY(hipMemcpyAsync(c->z[1], c->z_host + h.tok_begin, (size_t)h.T * 2, hipMemcpyHostToDevice,
+                               c->copy_stream));
+    }
+    HIP_TRY(hipEventRecord(c->slot_ready[s], c->copy_stream));
+    HIP_TRY(hipStreamWaitEvent(c->stream, c->slot_ready[s], 0));
+    write_padding_entries(c);
+    if (with_z && h.T > 0)
+        hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
+                           c->z[1], c->tok_id, c->z[0], h.T, h.tok_begin);
+    return launch_check("attaching a chunk");
+}
+
+// Streamed: the attached chunk's assignments z (word-major) go back to the host, and the
+// chunk's slot is free again once everything queued so far is done.
+int store_z_and_release(mlda_ctx* c, int32_t m, const uint16_t* z_word, bool store) {
+    const HostChunk& h = c->chunks[(size_t)m];
+    const int s = (int)((c->visits - 1) % 2);
+    if (store && h.T > 0) {
+        uint16_t* tmp = (z_word == c->z[0]) ? c->z[1] : c->z[0];
+        hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
+                           z_word, c->doc_map, tmp, h.T);
+        HIP_TRY(hipMemcpyAsync(c->z_host + h.tok_begin, tmp, (size_t)h.T * 2, hipMemcpyDeviceToHost,
+                               c->stream));
+        HIP_TRY(hipEventRecord(c->z_stored[(size_t)m], c->stream));
+    }
+    HIP_TRY(hipEventRecord(c->slot_free[s], c->stream));
+    return launch_check("storing a chunk's assignments");
+}
+
+// phi (into n_wk[which]) from the attached chunk's assignments z (word-major).  One chunk:
+// rows are stored and n_k follows; several: the chunk's counts are added to a phi that was
+// zeroed before the first chunk, and n_k is formed after the last (finish_model).
+int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
     using namespace mlda;
     const size_t hist_bytes = (size_t)c->K * 4;
-    if (c->n_split > 0) {
-        dim3 grid((unsigned)c->n_split, (unsigned)blocks_for(c->K, 256));
-        hipLaunchKernelGGL(zero_rows_kernel, grid, dim3(256), 0, c->stream, c->split_words, c->n_wk,
-                           c->K);
+    if (!c->streamed) {
+        if (c->n_split > 0) {
+            dim3 grid((unsigned)c->n_split, (unsigned)blocks_for(c->K, 256));
+            hipLaunchKernelGGL(zero_rows_kernel, grid, dim3(256), 0, c->stream, c->split_words,
+                               c->n_wk[which], c->K);
+        }
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream,
+                           c->n_k[which], (int64_t)c->K, 0);
     }
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream, c->n_k,
-                       (int64_t)c->K, 0);
     if (c->n_tiles > 0) {
-        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes,
-                           c->stream, c->segs, z, c->n_wk, c->K);
-        if ((int64_t)c->V * c->K * 2 < c->T) {
+        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes, c->stream,
+                           c->segs, z, c->n_wk[which], c->K);
+        if (c->streamed) {
+            // n_k after the last chunk
+        } else if ((int64_t)c->V * c->K * 2 < c->T) {
             // n_k as column sums of the fresh n_wk: fewer bytes than z and no LDS atomics
             const int words_per_slice = 64;
             dim3 grid((unsigned)blocks_for(c->K, 256), (unsigned)blocks_for(c->V, words_per_slice));
-            hipLaunchKernelGGL(topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream, c->n_wk,
-                               c->V, c->K, words_per_slice, c->n_k);
+            hipLaunchKernelGGL(topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream,
+                               c->n_wk[which], c->V, c->K, words_per_slice, c->n_k[which]);
         } else {
             const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
-            hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes,
-                               c->stream, z, c->T, c->n_k, c->K);
+            hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes, c->stream,
+                               z, c->T, c->n_k[which], c->K);
         }
     }
-    if (ev_phi) HIP_TRY(hipEventRecord(*ev_phi, c->stream));
+    return launch_check("phi rebuild kernels");
+}
+
+// Streamed: phi[which] starts at zero before the first chunk adds to it ...
+int begin_model(mlda_ctx* c, int which) {
+    const int64_t cells = (int64_t)c->V * c->K;
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
+                       c->n_wk[which], cells, 0);
+    return launch_check("fill_i32_kernel");
+}
+
+// ... and n_k[which] is its column sums after the last.
+int finish_model(mlda_ctx* c, int which) {
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream,
+                       c->n_k[which], (int64_t)c->K, 0);
+    const int words_per_slice = 64;
+    dim3 grid((unsigned)blocks_for(c->K, 256), (unsigned)blocks_for(c->V, words_per_slice));
+    hipLaunchKernelGGL(mlda::topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream, c->n_wk[which],
+                       c->V, c->K, words_per_slice, c->n_k[which]);
+    return launch_check("topic totals");
+}
+
+// theta rows of the attached chunk from its assignments z (word-major); leaves the rows' part
+// of the log-likelihood as one partial per workgroup in ll_partial[2 kLoglikBlocks ..].
+int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
+    using namespace mlda;
     if (c->D > 0) {
         const size_t theta_lds = theta_lds_bytes(c->K, c->packed);
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
@@ -213,20 +567,70 @@ int rebuild_counts(mlda_ctx* c, const uint16_t* z, hipEvent_t* ev_phi, hipEvent_
                                c->ll_partial + 2 * kLoglikBlocks);
     }
     c->rebuilds += 1;
-    if (ev_theta) HIP_TRY(hipEventRecord(*ev_theta, c->stream));
-    return launch_check("rebuild kernels");
+    return launch_check("theta rebuild kernel");
 }
 
+int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
+    if (c->n_tiles == 0) return MLDA_OK;
+    mlda::SampleArgs a;
+    a.tiles = c->tiles;
+    a.tok_slot = c->tok_slot;
+    a.tok_id = c->tok_id;
+    a.z_cur = z_cur;
+    a.z_next = z_next;
+    a.slots = c->slots;
+    a.n_wk = c->n_wk[c->model_cur];
+    a.n_k = c->n_k[c->model_cur];
+    a.K = c->K;
+    a.Kpad = c->Kpad;
+    a.alpha = c->alpha;
+    a.beta = c->beta;
+    a.beta_V = c->beta * (double)c->V;
+    a.seed = c->seed;
+    a.iter = (uint32_t)(c->iter + 1);
+    const int waves = sample_waves_for(c->K);
+    void* kernel_args[] = {&a};
+    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->packed), dim3((unsigned)c->n_tiles),
+                            dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
+    return launch_check("sample_kernel");
+}
+
+// Log-likelihood of the current state, one chunk: word side, document term, theta partials
+// left by the last rebuild_theta.
 int launch_loglik(mlda_ctx* c) {
     using namespace mlda;
     const int64_t cells = (int64_t)c->V * c->K;
-    hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->n_wk,
-                       cells, c->n_k, c->K, c->beta, (double)c->V * c->beta, c->lg_table_beta,
-                       c->ll_partial);
-    hipLaunchKernelGGL(loglik_doc_term_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
-                       c->doc_ptr, c->D, (double)c->K * c->alpha, c->ll_partial + kLoglikBlocks);
+    hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
+                       c->n_wk[c->model_cur], cells, c->n_k[c->model_cur], c->K, c->beta,
+                       (double)c->V * c->beta, c->lg_table_beta, c->ll_partial);
+    hipLaunchKernelGGL(loglik_doc_term_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->doc_ptr,
+                       c->D, (double)c->K * c->alpha, c->ll_partial + kLoglikBlocks);
     hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial,
-                       2 * kLoglikBlocks + c->theta_grid, c->ll_value);
+                       2 * kLoglikBlocks + c->theta_grid, (const double*)nullptr, 0, c->ll_scalars);
+    c->ll_fresh = true;
+    return launch_check("log-likelihood kernels");
+}
+
+// Streamed: the theta partials of the chunk just rebuilt are added to the running sum ...
+int add_theta_loglik(mlda_ctx* c, bool first) {
+    hipLaunchKernelGGL(mlda::loglik_final_kernel, dim3(1), dim3(256), 0, c->stream,
+                       c->ll_partial + 2 * kLoglikBlocks, c->D > 0 ? c->theta_grid : 0,
+                       (const double*)nullptr, first ? 0 : 1, c->ll_scalars + 1);
+    return launch_check("loglik_final_kernel");
+}
+
+// ... and the value is the word side plus that sum plus the documents' term (a constant of
+// the corpus, scalars[2]).
+int finish_loglik_streamed(mlda_ctx* c) {
+    using namespace mlda;
+    const int64_t cells = (int64_t)c->V * c->K;
+    hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
+                       c->n_wk[c->model_cur], cells, c->n_k[c->model_cur], c->K, c->beta,
+                       (double)c->V * c->beta, c->lg_table_beta, c->ll_partial);
+    hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, kLoglikBlocks,
+                       (const double*)(c->ll_scalars + 1), 0, c->ll_scalars);
+    hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, 0,
+                       (const double*)(c->ll_scalars + 2), 1, c->ll_scalars);
     c->ll_fresh = true;
     return launch_check("log-likelihood kernels");
 }
@@ -235,6 +639,204 @@ int need_state(const mlda_ctx* c) {
     if (!c) return fail(MLDA_EINVAL, "null context");
     if (!c->has_state)
         return fail(MLDA_EINVAL, "no topic assignments yet: call mlda_init_random or mlda_set_assignments");
+    return MLDA_OK;
+}
+
+int check_corpus(const int64_t* doc_ptr, const int32_t* word_ids, bool need_words, int64_t D, int32_t V,
+                 int32_t K, double alpha, double beta) {
+    if (!doc_ptr) return fail(MLDA_EINVAL, "doc_ptr is null");
+    if (D < 0 || V < 1) return fail(MLDA_EINVAL, "need D >= 0 and V >= 1");
+    if (K < 1 || K > 65535) return fail(MLDA_EINVAL, "K must be in [1, 65535] (16-bit topic indices)");
+    if (!(alpha > 0.0) || !(beta > 0.0) || !std::isfinite(alpha) || !std::isfinite(beta))
+        return fail(MLDA_EINVAL, "alpha and beta must be positive and finite");
+    if (doc_ptr[0] != 0) return fail(MLDA_EINVAL, "doc_ptr[0] must be 0");
+    for (int64_t d = 0; d < D; ++d)
+        if (doc_ptr[d + 1] < doc_ptr[d]) return fail(MLDA_EINVAL, "doc_ptr must be non-decreasing");
+    if (doc_ptr[D] >= ((int64_t)1 << 31)) return fail(MLDA_EINVAL, "2^31 or more tokens");
+    if (need_words && doc_ptr[D] > 0 && !word_ids) return fail(MLDA_EINVAL, "word_ids is null");
+    return MLDA_OK;
+}
+
+int check_workspace(void* dev_workspace, size_t have, size_t need) {
+    if (!dev_workspace) return fail(MLDA_EINVAL, "dev_workspace is null");
+    if (((uintptr_t)dev_workspace) % kAlign != 0)
+        return fail(MLDA_EINVAL, "dev_workspace must be 256-byte aligned");
+    if (have < need)
+        return fail(MLDA_ENOMEM, "workspace has " + std::to_string(have) + " bytes, need " +
+                                     std::to_string(need));
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, dev_workspace);
+    if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(MLDA_EINVAL, "dev_workspace is not device memory");
+    }
+    return MLDA_OK;
+}
+
+size_t streamed_workspace_bound(const int64_t* doc_ptr, int64_t D, int32_t V, int32_t K, int32_t M) {
+    size_t chunk = 0;
+    for (int32_t m = 0; m < M; ++m) {
+        const int64_t a = chunk_first(doc_ptr, D, M, m), b = chunk_first(doc_ptr, D, M, m + 1);
+        chunk = std::max(chunk, chunk_layout_bound(b - a, doc_ptr[b] - doc_ptr[a], V, K).total);
+    }
+    return model_layout(V, K, true).total + 2 * chunk;
+}
+
+// Everything mlda_create and mlda_create_streamed share: device limits, the model's buffers
+// and tables.  `chunks` are prepared; `base` is the workspace.
+int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
+    c->n_wk[0] = (int32_t*)(base + ML.n_wk[0]);
+    c->n_wk[1] = (int32_t*)(base + ML.n_wk[1]);
+    c->n_k[0] = (int32_t*)(base + ML.n_k[0]);
+    c->n_k[1] = (int32_t*)(base + ML.n_k[1]);
+    c->ll_partial = (double*)(base + ML.ll_partial);
+    c->ll_scalars = (double*)(base + ML.ll_scalars);
+    c->lg_table = (double*)(base + ML.lg_table);
+    c->lg_table_beta = c->lg_table + (mlda::kLgTable + 1);
+    c->row_entries = (unsigned long long*)(base + ML.row_entries);
+
+    hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
+                       c->stream, c->lg_table, c->alpha);
+    hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
+                       c->stream, c->lg_table_beta, c->beta);
+    // rows of words without tokens are never written again: start phi at zero
+    const int64_t cells = (int64_t)c->V * c->K;
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
+                       c->n_wk[0], cells, 0);
+    RC_TRY(launch_check("model set-up kernels"));
+    const void* samplers[] = {sample_kernel_for(c->K, true), sample_kernel_for(c->K, false)};
+    if (c->sample_lds > 48 * 1024)
+        for (const void* k : samplers)
+            HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->sample_lds));
+    if ((size_t)c->K * 4 > 48 * 1024) {
+        HIP_TRY(hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
+        HIP_TRY(hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
+        HIP_TRY(hipFuncSetAttribute((const void*)mlda::theta_rows_kernel<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)mlda::theta_lds_bytes(c->K, true)));
+        HIP_TRY(hipFuncSetAttribute((const void*)mlda::theta_rows_kernel<false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)mlda::theta_lds_bytes(c->K, false)));
+    }
+    return MLDA_OK;
+}
+
+int device_limits(mlda_ctx* c) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(hipDeviceGetAttribute(&c->lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    // one zero entry of p* past the last topic: padding entries of theta rows point at it
+    const int32_t dense_group = mlda::dense_group(sample_waves_for(c->K));
+    c->Kpad = (c->K + dense_group) / dense_group * dense_group;
+    c->sample_lds = mlda::sample_lds_bytes(c->Kpad, sample_waves_for(c->K));
+    if (c->sample_lds > (size_t)c->lds_limit)
+        return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " needs " + std::to_string(c->sample_lds) +
+                                      " bytes of LDS per workgroup, the device allows " +
+                                      std::to_string(c->lds_limit));
+    return MLDA_OK;
+}
+
+void destroy(mlda_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    if (c->copy_stream) {
+        (void)hipStreamSynchronize(c->copy_stream);
+        (void)hipStreamDestroy(c->copy_stream);
+    }
+    for (hipEvent_t ev : c->events) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : c->z_stored) (void)hipEventDestroy(ev);
+    for (int s = 0; s < 2; ++s) {
+        if (c->slot_ready[s]) (void)hipEventDestroy(c->slot_ready[s]);
+        if (c->slot_free[s]) (void)hipEventDestroy(c->slot_free[s]);
+    }
+    if (c->z_host) (void)hipHostFree(c->z_host);
+    delete c;
+}
+
+// Rows of theta of the attached chunk, unpacked into the caller's CSR arrays (documents
+// h.d_begin ..; row_ptr already holds the row starts).
+int fetch_rows(mlda_ctx* c, std::vector<uint2>& rec, std::vector<unsigned char>& slots) {
+    try {
+        rec.resize((size_t)c->D);
+        slots.resize(c->slots_bytes);
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    if (c->D > 0)
+        HIP_TRY(hipMemcpyAsync(rec.data(), c->row_rec, (size_t)c->D * 8, hipMemcpyDeviceToHost, c->stream));
+    if (c->slots_bytes > 0)
+        HIP_TRY(hipMemcpyAsync(slots.data(), c->slots, c->slots_bytes, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+int fetch_row_rec(mlda_ctx* c, std::vector<uint2>& rec) {
+    try { rec.resize((size_t)c->D); } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    if (c->D > 0)
+        HIP_TRY(hipMemcpyAsync(rec.data(), c->row_rec, (size_t)c->D * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return MLDA_OK;
+}
+
+void unpack_rows(const mlda_ctx* c, const std::vector<uint2>& rec, const std::vector<unsigned char>& slots,
+                 const int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
+    for (int64_t d = 0; d < c->D; ++d) {
+        const uint32_t nnz = rec[(size_t)d].y, pad = (nnz + 3u) & ~3u;
+        const unsigned char* base = slots.data() + (size_t)rec[(size_t)d].x * 16 + mlda::kRowHeader;
+        if (nnz == 0) continue;
+        if (c->packed) {
+            const uint32_t* ent = reinterpret_cast<const uint32_t*>(base);
+            for (uint32_t j = 0; j < nnz; ++j) {
+                counts[row_ptr[d] + j] = (int32_t)(ent[j] >> 18);
+                topics[row_ptr[d] + j] = (uint16_t)((ent[j] >> 2) & 0xffffu);
+            }
+        } else {
+            std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
+            std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
+        }
+    }
+}
+
+// Streamed: phi and n_k of the assignments in z_host (after init or set_assignments);
+// `init`: the assignments are drawn on the device first and stored.
+int rebuild_model_streamed(mlda_ctx* c, bool init) {
+    RC_TRY(begin_model(c, c->model_cur));
+    for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
+        if (c->chunks[(size_t)m].D == 0) continue;
+        RC_TRY(attach(c, m, !init));
+        if (init && c->T > 0)
+            hipLaunchKernelGGL(mlda::init_topics_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
+                               c->tok_id, c->z[0], c->T, c->K, c->seed);
+        RC_TRY(rebuild_phi(c, c->z[0], c->model_cur));
+        RC_TRY(store_z_and_release(c, m, c->z[0], init));
+    }
+    return finish_model(c, c->model_cur);
+}
+
+// Streamed: the theta rows of every chunk are rebuilt in turn from z_host; `visit` sees each
+// attached chunk with its rows in place.  Also leaves the log-likelihood's theta sum.
+template <class F>
+int for_each_chunk_rows(mlda_ctx* c, F&& visit) {
+    bool first = true;
+    for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
+        if (c->chunks[(size_t)m].D == 0) continue;
+        RC_TRY(attach(c, m, true));
+        RC_TRY(rebuild_theta(c, c->z[0]));
+        RC_TRY(add_theta_loglik(c, first));
+        first = false;
+        RC_TRY(visit(c->chunks[(size_t)m]));
+        RC_TRY(store_z_and_release(c, m, c->z[0], false));
+    }
+    if (first) {            // no documents at all: the sum is empty
+        hipLaunchKernelGGL(mlda::loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, 0,
+                           (const double*)nullptr, 0, c->ll_scalars + 1);
+        RC_TRY(launch_check("loglik_final_kernel"));
+    }
     return MLDA_OK;
 }
 
@@ -259,7 +861,16 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
     if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
     if (D < 0 || T < 0 || V < 1 || K < 1 || K > 65535 || T >= ((int64_t)1 << 31))
         return fail(MLDA_EINVAL, "need D >= 0, 0 <= T < 2^31, V >= 1, 1 <= K <= 65535");
-    *bytes = layout_bound(D, T, V, K).total;
+    *bytes = model_layout(V, K, false).total + chunk_layout_bound(D, T, V, K).total;
+    return MLDA_OK;
+}
+
+int mlda_workspace_bytes_streamed(const int64_t* doc_ptr, int64_t D, int32_t V, int32_t K,
+                                  int32_t n_chunks, size_t* bytes) {
+    if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
+    RC_TRY(check_corpus(doc_ptr, nullptr, false, D, V, K, 1.0, 1.0));
+    if (n_chunks < 1) return fail(MLDA_EINVAL, "n_chunks must be >= 1");
+    *bytes = streamed_workspace_bound(doc_ptr, D, V, K, n_chunks);
     return MLDA_OK;
 }
 
@@ -268,295 +879,127 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                 void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out) return fail(MLDA_EINVAL, "out is null");
     *out = nullptr;
-    if (!doc_ptr) return fail(MLDA_EINVAL, "doc_ptr is null");
-    if (D < 0 || V < 1) return fail(MLDA_EINVAL, "need D >= 0 and V >= 1");
-    if (K < 1 || K > 65535) return fail(MLDA_EINVAL, "K must be in [1, 65535] (16-bit topic indices)");
-    if (!(alpha > 0.0) || !(beta > 0.0) || !std::isfinite(alpha) || !std::isfinite(beta))
-        return fail(MLDA_EINVAL, "alpha and beta must be positive and finite");
-    if (doc_ptr[0] != 0) return fail(MLDA_EINVAL, "doc_ptr[0] must be 0");
-    for (int64_t d = 0; d < D; ++d)
-        if (doc_ptr[d + 1] < doc_ptr[d]) return fail(MLDA_EINVAL, "doc_ptr must be non-decreasing");
+    RC_TRY(check_corpus(doc_ptr, word_ids, true, D, V, K, alpha, beta));
     const int64_t T = doc_ptr[D];
-    if (T >= ((int64_t)1 << 31)) return fail(MLDA_EINVAL, "2^31 or more tokens");
-    if (T > 0 && !word_ids) return fail(MLDA_EINVAL, "word_ids is null");
-    if (!dev_workspace) return fail(MLDA_EINVAL, "dev_workspace is null");
-    if (((uintptr_t)dev_workspace) % kAlign != 0)
-        return fail(MLDA_EINVAL, "dev_workspace must be 256-byte aligned");
     size_t need_bound = 0;
     if (mlda_workspace_bytes(D, T, V, K, &need_bound) != MLDA_OK) return MLDA_EINVAL;
-    if (workspace_bytes < need_bound)
-        return fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
-                                     std::to_string(need_bound));
-    {
-        hipPointerAttribute_t attr;
-        hipError_t e = hipPointerGetAttributes(&attr, dev_workspace);
-        if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
-            (void)hipGetLastError();
-            return fail(MLDA_EINVAL, "dev_workspace is not device memory");
-        }
-    }
-
-    int dev = 0, n_cus = 0, lds_limit = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
-    HIP_TRY(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-    // one zero entry of p* past the last topic: padding entries of theta rows point at it
-    const int32_t dense_group = mlda::dense_group(sample_waves_for(K));
-    const int32_t Kpad = (K + dense_group) / dense_group * dense_group;
-    const size_t sample_lds = mlda::sample_lds_bytes(Kpad, sample_waves_for(K));
-    if (sample_lds > (size_t)lds_limit)
-        return fail(MLDA_ENOTSUP, "K = " + std::to_string(K) + " needs " + std::to_string(sample_lds) +
-                                      " bytes of LDS per workgroup, the device allows " +
-                                      std::to_string(lds_limit));
-
-    // ---- word-first order (Section 6.1.2).  Inside a word the tokens are put in order of
-    // falling document length, so that the four theta rows a wave walks together have
-    // similar lengths; any order inside a word gives the same result, because the uniforms
-    // are keyed by the caller's token index.  Stable counting sort by word over chunks of
-    // the length-sorted document sequence.
-    int64_t longest_doc = 0;
-    for (int64_t d = 0; d < D; ++d) longest_doc = std::max(longest_doc, doc_ptr[d + 1] - doc_ptr[d]);
-    // a count never exceeds the document's length: 4-byte theta entries if 14 bits hold it
-    const bool packed = longest_doc <= mlda::PackedRows::kMaxCount;
-    const int entry_bytes = packed ? mlda::PackedRows::kEntryBytes : mlda::SplitRows::kEntryBytes;
-    std::vector<int32_t> doc_order;
-    std::vector<int64_t> order_tokens;           // tokens before each position of doc_order
-    try {
-        doc_order.resize((size_t)D);
-        order_tokens.resize((size_t)D + 1);
-        const int64_t max_len = longest_doc;
-        std::vector<int64_t> len_start((size_t)max_len + 2, 0);
-        for (int64_t d = 0; d < D; ++d) ++len_start[(size_t)(max_len - (doc_ptr[d + 1] - doc_ptr[d])) + 1];
-        for (int64_t l = 0; l <= max_len; ++l) len_start[(size_t)l + 1] += len_start[(size_t)l];
-        for (int64_t d = 0; d < D; ++d)
-            doc_order[(size_t)len_start[(size_t)(max_len - (doc_ptr[d + 1] - doc_ptr[d]))]++] = (int32_t)d;
-        order_tokens[0] = 0;
-        for (int64_t i = 0; i < D; ++i) {
-            const int64_t d = doc_order[(size_t)i];
-            order_tokens[(size_t)i + 1] = order_tokens[(size_t)i] + (doc_ptr[d + 1] - doc_ptr[d]);
-        }
-    } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
-    const int n_chunks = (int)std::max<int64_t>(
-        1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 32, T / 65536 + 1}));
-    std::vector<std::vector<int32_t>> chunk_hist(n_chunks);
-    std::vector<int> chunk_bad(n_chunks, 0);
-    // chunk c holds the documents doc_order[chunk_lo(c) .. chunk_lo(c+1)), about T/n_chunks tokens
-    auto chunk_lo = [&](int c) -> int64_t {
-        if (c >= n_chunks) return D;
-        const int64_t want = T / n_chunks * c;
-        return std::lower_bound(order_tokens.begin(), order_tokens.end(), want) - order_tokens.begin();
-    };
-    try {
-        parallel_chunks(n_chunks, [&](int c) {
-            auto& h = chunk_hist[c];
-            h.assign((size_t)V, 0);
-            for (int64_t i = chunk_lo(c); i < chunk_lo(c + 1); ++i) {
-                const int64_t d = doc_order[(size_t)i];
-                for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; ++t) {
-                    const int32_t w = word_ids[t];
-                    if (w < 0 || w >= V) { chunk_bad[c] = 1; return; }
-                    ++h[w];
-                }
-            }
-        });
-    } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
-    for (int c = 0; c < n_chunks; ++c)
-        if (chunk_bad[c]) return fail(MLDA_EINVAL, "word id outside [0, V)");
-
-    std::vector<uint32_t> tok_slot;
-    std::vector<int32_t> word_ptr((size_t)V + 1, 0), tok_id, doc_map, doc_ptr32, split_words;
-    std::vector<uint2> row_rec;
-    std::vector<mlda::DocRec> doc_recs;
-    std::vector<mlda::Tile> tiles, segs;
-    size_t slots_bytes = 0;
-    try {
-        for (int32_t v = 0; v < V; ++v) {
-            int32_t n = 0;
-            for (int c = 0; c < n_chunks; ++c) {
-                const int32_t h = chunk_hist[c][v];
-                chunk_hist[c][v] = n;          // becomes the chunk's offset inside the word
-                n += h;
-            }
-            word_ptr[v + 1] = word_ptr[v] + n;
-        }
-        // ---- theta row slots: fixed capacity min(N_d, K), so rows never move; laid out in the
-        // order the documents are worked on, so that rows in use together are neighbours
-        row_rec.resize((size_t)D);
-        slots_bytes = kSlotAlign;       // the buffer starts with four padding entries
-        for (int64_t i = 0; i < D; ++i) {
-            const int64_t d = doc_order[(size_t)i];
-            const int64_t cap = std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K);
-            if (slots_bytes / 16 > 0xffffffffull)
-                return fail(MLDA_ENOTSUP, "theta rows need more than 64 GiB");
-            row_rec[(size_t)d] = make_uint2((uint32_t)(slots_bytes / 16), 0u);
-            slots_bytes += slot_bytes_for(cap, entry_bytes);
-        }
-        tok_slot.resize((size_t)T);
-        tok_id.resize((size_t)T);
-        doc_map.resize((size_t)T);
-        parallel_chunks(n_chunks, [&](int c) {
-            auto& start = chunk_hist[c];
-            for (int64_t i = chunk_lo(c); i < chunk_lo(c + 1); ++i) {
-                const int64_t d = doc_order[(size_t)i];
-                for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; ++t) {
-                    const int32_t w = word_ids[t];
-                    const int32_t pos = word_ptr[w] + start[w]++;
-                    tok_id[pos] = (int32_t)t;
-                    tok_slot[pos] = row_rec[(size_t)d].x;
-                    doc_map[t] = pos;
-                }
-            }
-        });
-        chunk_hist.clear();
-
-        doc_ptr32.resize((size_t)D + 1);
-        for (int64_t d = 0; d <= D; ++d) doc_ptr32[d] = (int32_t)doc_ptr[d];
-
-        doc_recs.resize((size_t)D);
-        for (int64_t i = 0; i < D; ++i) {
-            const int64_t d = doc_order[(size_t)i];
-            doc_recs[(size_t)i] = mlda::DocRec{(int32_t)doc_ptr[d], (int32_t)(doc_ptr[d + 1] - doc_ptr[d]),
-                                              row_rec[(size_t)d].x, (int32_t)d};
-        }
-
-        // ---- tiles of one word each, largest first (Section 6.1.2)
-        const int32_t tile = tile_tokens_for(K);
-        for (int32_t v = 0; v < V; ++v) {
-            const int32_t n = word_ptr[v + 1] - word_ptr[v];
-            for (int32_t b = 0; b < n; b += tile)
-                tiles.push_back(mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), n <= tile ? 1 : 0});
-            if (n > kPhiSegment) split_words.push_back(v);
-            for (int32_t b = 0; b < n; b += kPhiSegment)
-                segs.push_back(mlda::Tile{v, word_ptr[v] + b, std::min(kPhiSegment, n - b),
-                                          n <= kPhiSegment ? 1 : 0});
-        }
-        auto larger_first = [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; };
-        // Sampling tiles run in the order of their first document (longest documents first),
-        // not word by word: tiles of different words that are in flight together then walk the
-        // theta rows of the same documents, which are fetched from HBM once instead of once
-        // per heavy word.  (The paper issues the tiles of heavy words first, Section 6.1.2;
-        // here the long-row tiles come first, which also keeps the tail short.)
-        // (slot offsets rise in that order)
-        std::stable_sort(tiles.begin(), tiles.end(), [&](const mlda::Tile& a, const mlda::Tile& b) {
-            return tok_slot[(size_t)a.begin] < tok_slot[(size_t)b.begin];
-        });
-        std::stable_sort(segs.begin(), segs.end(), larger_first);
-    } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
-
-    const Layout L = layout_for(D, T, V, K, slots_bytes, tiles.size(), segs.size(), split_words.size());
-    if (L.total > workspace_bytes)
-        return fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
-                                     std::to_string(L.total));
-
+    RC_TRY(check_workspace(dev_workspace, workspace_bytes, need_bound));
     mlda_ctx* c = new (std::nothrow) mlda_ctx();
     if (!c) return fail(MLDA_ENOMEM, "out of host memory");
-    c->D = D; c->T = T; c->V = V; c->K = K; c->Kpad = Kpad;
+    c->D_all = D; c->T_all = T; c->V = V; c->K = K;
     c->alpha = alpha; c->beta = beta; c->seed = seed;
     c->stream = (hipStream_t)hip_stream;
-    c->n_cus = n_cus; c->lds_limit = lds_limit; c->sample_lds = sample_lds;
-    c->n_tiles = (int32_t)tiles.size();
-    c->packed = packed;
-    {
-        const size_t theta_lds = mlda::theta_lds_bytes(K, packed);
-        // 16 one-wave workgroups per CU: enough to hide the gathers' latency; more of them
-        // touch more lines of z at once than an XCD's L2 holds, and neighbours stop sharing
-        const int per_cu = std::max(1, std::min(16, (int)(144 * 1024 / theta_lds)));
-        c->theta_grid = (int32_t)std::min<int64_t>({D, (int64_t)n_cus * per_cu, (int64_t)kMaxThetaGrid});
+    int rc = device_limits(c);
+    if (rc == MLDA_OK) {
+        try { c->chunks = std::vector<HostChunk>(1); } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
     }
-    c->n_segs = (int32_t)segs.size();
-    c->n_split = (int32_t)split_words.size();
-    c->slots_bytes = slots_bytes;
-    c->doc_ptr_host.assign(doc_ptr, doc_ptr + D + 1);
+    if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->chunks[0]);
+    const ModelLayout ML = model_layout(V, K, false);
+    if (rc == MLDA_OK && ML.total + c->chunks[0].L.total > workspace_bytes)
+        rc = fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
+                                   std::to_string(ML.total + c->chunks[0].L.total));
+    if (rc == MLDA_OK) {
+        unsigned char* base = (unsigned char*)dev_workspace;
+        HostChunk& h = c->chunks[0];
+        c->slot_base[0] = base + ML.total;
+        point_at(c, h, c->slot_base[0]);
+        hipError_t e = hipSuccess;
+        if (h.L.static_bytes > 0)
+            e = hipMemcpyAsync(c->slot_base[0], h.arena, h.L.static_bytes, hipMemcpyHostToDevice, c->stream);
+        if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
+        if (rc == MLDA_OK) { write_padding_entries(c); rc = finish_create(c, base, ML); }
+        if (rc == MLDA_OK) {
+            e = hipStreamSynchronize(c->stream);
+            if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
+        }
+        h.release();        // the corpus now lives on the device
+    }
+    if (rc != MLDA_OK) { destroy(c); return rc; }
+    *out = c;
+    return MLDA_OK;
+}
 
-    unsigned char* p = (unsigned char*)dev_workspace;
-    auto take = [&](size_t bytes) { unsigned char* q = p; p += bytes; return q; };
-    c->tok_slot = (uint32_t*)take(L.tok_slot);
-    c->tok_id = (int32_t*)take(L.tok_id);
-    c->doc_map = (int32_t*)take(L.doc_map);
-    c->z[0] = (uint16_t*)take(L.z0);
-    c->z[1] = (uint16_t*)take(L.z1);
-    c->doc_ptr = (int32_t*)take(L.doc_ptr);
-    c->doc_order = (mlda::DocRec*)take(L.doc_order);
-    c->row_rec = (uint2*)take(L.row_rec);
-    c->slots = take(L.slots);
-    c->n_wk = (int32_t*)take(L.n_wk);
-    c->n_k = (int32_t*)take(L.n_k);
-    c->tiles = (mlda::Tile*)take(L.tiles);
-    c->segs = (mlda::Tile*)take(L.segs);
-    c->split_words = (int32_t*)take(L.split);
-    c->ll_partial = (double*)take(L.ll_partial);
-    c->ll_value = (double*)take(L.ll_value);
-    c->lg_table = (double*)take(L.lg_table);
-    c->lg_table_beta = c->lg_table + (mlda::kLgTable + 1);
-    c->row_entries = (unsigned long long*)take(L.row_entries);
-
-    auto up = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
-        if (bytes == 0) return hipSuccess;
-        return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->stream);
+int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
+                         int32_t V, int32_t K, double alpha, double beta, uint64_t seed, int32_t n_chunks,
+                         void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(MLDA_EINVAL, "out is null");
+    *out = nullptr;
+    RC_TRY(check_corpus(doc_ptr, word_ids, true, D, V, K, alpha, beta));
+    if (n_chunks < 1) return fail(MLDA_EINVAL, "n_chunks must be >= 1");
+    const int64_t T = doc_ptr[D];
+    RC_TRY(check_workspace(dev_workspace, workspace_bytes,
+                           streamed_workspace_bound(doc_ptr, D, V, K, n_chunks)));
+    mlda_ctx* c = new (std::nothrow) mlda_ctx();
+    if (!c) return fail(MLDA_ENOMEM, "out of host memory");
+    c->D_all = D; c->T_all = T; c->V = V; c->K = K;
+    c->alpha = alpha; c->beta = beta; c->seed = seed;
+    c->stream = (hipStream_t)hip_stream;
+    c->streamed = true;
+    int rc = device_limits(c);
+    if (rc == MLDA_OK) {
+        try {
+            c->chunks = std::vector<HostChunk>((size_t)n_chunks);
+            c->z_stored.assign((size_t)n_chunks, nullptr);
+        } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
+    }
+    size_t chunk_bytes = 0;
+    for (int32_t m = 0; rc == MLDA_OK && m < n_chunks; ++m) {
+        rc = prepare_chunk(doc_ptr, word_ids, chunk_first(doc_ptr, D, n_chunks, m),
+                           chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, c->chunks[(size_t)m]);
+        if (rc == MLDA_OK) chunk_bytes = std::max(chunk_bytes, c->chunks[(size_t)m].L.total);
+    }
+    const ModelLayout ML = model_layout(V, K, true);
+    if (rc == MLDA_OK && ML.total + 2 * chunk_bytes > workspace_bytes)
+        rc = fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
+                                   std::to_string(ML.total + 2 * chunk_bytes));
+    auto hip_ok = [&](hipError_t e, const char* what) {
+        if (rc == MLDA_OK && e != hipSuccess) rc = fail(MLDA_EHIP, std::string(what) + ": " + hipGetErrorString(e));
     };
-    hipError_t e = hipSuccess;
-    if (e == hipSuccess) e = up(c->tok_slot, tok_slot.data(), (size_t)T * 4);
-    if (e == hipSuccess) e = up(c->tok_id, tok_id.data(), (size_t)T * 4);
-    if (e == hipSuccess) e = up(c->doc_map, doc_map.data(), (size_t)T * 4);
-    if (e == hipSuccess) e = up(c->doc_ptr, doc_ptr32.data(), (size_t)(D + 1) * 4);
-    if (e == hipSuccess) e = up(c->doc_order, doc_recs.data(), (size_t)D * sizeof(mlda::DocRec));
-    if (e == hipSuccess) e = up(c->row_rec, row_rec.data(), (size_t)D * 8);
-    // what a lane of the sampler reads when it has no entries of its own (count 0, topic K)
-    const uint32_t pad_entries[4] = {(uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2, (uint32_t)K << 2};
-    if (e == hipSuccess) e = up(c->slots, pad_entries, sizeof(pad_entries));
-    if (e == hipSuccess) e = up(c->tiles, tiles.data(), tiles.size() * sizeof(mlda::Tile));
-    if (e == hipSuccess) e = up(c->segs, segs.data(), segs.size() * sizeof(mlda::Tile));
-    if (e == hipSuccess) e = up(c->split_words, split_words.data(), split_words.size() * 4);
-    if (e == hipSuccess) {
-        hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
-                           c->stream, c->lg_table, alpha);
-        hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
-                           c->stream, c->lg_table_beta, beta);
-        // rows of words without tokens are never written again: start phi at zero
-        const int64_t cells = (int64_t)V * K;
-        hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
-                           c->n_wk, cells, 0);
-        e = hipGetLastError();
+    if (rc == MLDA_OK) {
+        unsigned char* base = (unsigned char*)dev_workspace;
+        c->slot_base[0] = base + ML.total;
+        c->slot_base[1] = c->slot_base[0] + chunk_bytes;
+        void* zh = nullptr;
+        hip_ok(hipHostMalloc(&zh, std::max<size_t>((size_t)T * 2, 1), hipHostMallocDefault), "hipHostMalloc");
+        c->z_host = (uint16_t*)zh;
+        // every stream at the default priority
+        hip_ok(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        for (int s = 0; s < 2; ++s) {
+            hip_ok(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming), "hipEventCreateWithFlags");
+            hip_ok(hipEventCreateWithFlags(&c->slot_free[s], hipEventDisableTiming), "hipEventCreateWithFlags");
+            if (rc == MLDA_OK) hip_ok(hipEventRecord(c->slot_free[s], c->stream), "hipEventRecord");
+        }
+        for (int32_t m = 0; m < n_chunks; ++m) {
+            hip_ok(hipEventCreateWithFlags(&c->z_stored[(size_t)m], hipEventDisableTiming), "hipEventCreateWithFlags");
+            if (rc == MLDA_OK) hip_ok(hipEventRecord(c->z_stored[(size_t)m], c->stream), "hipEventRecord");
+        }
+        if (rc == MLDA_OK) rc = finish_create(c, base, ML);
+        if (rc == MLDA_OK) {
+            // the documents' term of the log-likelihood never changes
+            double doc_term = 0.0;
+            const double ka = (double)K * alpha, lg_ka = std::lgamma(ka);
+            for (int64_t d = 0; d < D; ++d) doc_term += lg_ka - std::lgamma((double)(doc_ptr[d + 1] - doc_ptr[d]) + ka);
+            hip_ok(hipMemcpyAsync(c->ll_scalars + 2, &doc_term, 8, hipMemcpyHostToDevice, c->stream), "hipMemcpyAsync");
+            hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize");
+        }
     }
-    if (e == hipSuccess && sample_lds > 48 * 1024)
-        e = hipFuncSetAttribute(sample_kernel_for(K, packed),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sample_lds);
-    if (e == hipSuccess && (size_t)K * 4 > 48 * 1024) {
-        e = hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, K * 4);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(packed ? (const void*)mlda::theta_rows_kernel<true>
-                                           : (const void*)mlda::theta_rows_kernel<false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)mlda::theta_lds_bytes(K, packed));
-    }
-    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    if (e != hipSuccess) {
-        delete c;
-        return fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
-    }
+    if (rc != MLDA_OK) { destroy(c); return rc; }
     *out = c;
     return MLDA_OK;
 }
 
 int mlda_init_random(mlda_ctx* c) {
     if (!c) return fail(MLDA_EINVAL, "null context");
-    if (c->T > 0)
-        hipLaunchKernelGGL(mlda::init_topics_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
-                           c->stream, c->tok_id, c->z[c->cur], c->T, c->K, c->seed);
-    int rc = launch_check("init_topics_kernel");
-    if (rc != MLDA_OK) return rc;
-    rc = rebuild_counts(c, c->z[c->cur], nullptr, nullptr);
-    if (rc != MLDA_OK) return rc;
+    if (c->streamed) {
+        RC_TRY(rebuild_model_streamed(c, true));
+    } else {
+        if (c->T > 0)
+            hipLaunchKernelGGL(mlda::init_topics_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                               c->stream, c->tok_id, c->z[c->cur], c->T, c->K, c->seed);
+        RC_TRY(launch_check("init_topics_kernel"));
+        RC_TRY(rebuild_phi(c, c->z[c->cur], 0));
+        RC_TRY(rebuild_theta(c, c->z[c->cur]));
+    }
     c->iter = 0;
     c->has_state = true;
     c->ll_fresh = false;
@@ -565,29 +1008,75 @@ int mlda_init_random(mlda_ctx* c) {
 
 int mlda_set_assignments(mlda_ctx* c, const uint16_t* z, int32_t iter) {
     if (!c) return fail(MLDA_EINVAL, "null context");
-    if (c->T > 0 && !z) return fail(MLDA_EINVAL, "z is null");
+    if (c->T_all > 0 && !z) return fail(MLDA_EINVAL, "z is null");
     if (iter < 0) return fail(MLDA_EINVAL, "iter must be >= 0");
-    for (int64_t t = 0; t < c->T; ++t)
+    for (int64_t t = 0; t < c->T_all; ++t)
         if (z[t] >= c->K) return fail(MLDA_EINVAL, "topic >= K in z");
-    if (c->T > 0) {
-        uint16_t* tmp = c->z[c->cur ^ 1];
-        HIP_TRY(hipMemcpyAsync(tmp, z, (size_t)c->T * 2, hipMemcpyHostToDevice, c->stream));
-        hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
-                           c->stream, tmp, c->tok_id, c->z[c->cur], c->T);
-        HIP_TRY(hipStreamSynchronize(c->stream));     // the caller's z may go away after return
+    if (c->streamed) {
+        HIP_TRY(hipStreamSynchronize(c->stream));
+        HIP_TRY(hipStreamSynchronize(c->copy_stream));
+        if (c->T_all > 0) std::memcpy(c->z_host, z, (size_t)c->T_all * 2);
+        RC_TRY(rebuild_model_streamed(c, false));
+    } else {
+        if (c->T > 0) {
+            uint16_t* tmp = c->z[c->cur ^ 1];
+            HIP_TRY(hipMemcpyAsync(tmp, z, (size_t)c->T * 2, hipMemcpyHostToDevice, c->stream));
+            hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                               c->stream, tmp, c->tok_id, c->z[c->cur], c->T, (int64_t)0);
+            HIP_TRY(hipStreamSynchronize(c->stream));     // the caller's z may go away after return
+        }
+        RC_TRY(rebuild_phi(c, c->z[c->cur], 0));
+        RC_TRY(rebuild_theta(c, c->z[c->cur]));
     }
-    int rc = rebuild_counts(c, c->z[c->cur], nullptr, nullptr);
-    if (rc != MLDA_OK) return rc;
     c->iter = iter;
     c->has_state = true;
     c->ll_fresh = false;
     return MLDA_OK;
 }
 
+// One iteration with several chunks (Algorithm 1, WorkSchedule2; Section 4: every chunk
+// samples against the phi of the iteration's start, the new phi is the sum over chunks).
+static int step_streamed(mlda_ctx* c, bool loglik) {
+    const int next = c->model_cur ^ 1;
+    RC_TRY(begin_model(c, next));
+    bool first = true;
+    for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
+        if (c->chunks[(size_t)m].D == 0) continue;
+        RC_TRY(attach(c, m, true));
+        RC_TRY(rebuild_theta(c, c->z[0]));             // theta is not kept between visits
+        RC_TRY(launch_sampler(c, c->z[0], c->z[1]));
+        RC_TRY(rebuild_phi(c, c->z[1], next));
+        if (loglik) {
+            RC_TRY(rebuild_theta(c, c->z[1]));
+            RC_TRY(add_theta_loglik(c, first));
+            first = false;
+        }
+        RC_TRY(store_z_and_release(c, m, c->z[1], true));
+    }
+    RC_TRY(finish_model(c, next));
+    c->model_cur = next;
+    c->iter += 1;
+    c->ll_fresh = false;
+    if (loglik) {
+        if (first) {
+            hipLaunchKernelGGL(mlda::loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, 0,
+                               (const double*)nullptr, 0, c->ll_scalars + 1);
+            RC_TRY(launch_check("loglik_final_kernel"));
+        }
+        RC_TRY(finish_loglik_streamed(c));
+    }
+    return MLDA_OK;
+}
+
 int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (n_iters < 0) return fail(MLDA_EINVAL, "n_iters must be >= 0");
+    if (c->streamed) {
+        c->timed_iters = 0;
+        c->last_step_iters = 0;
+        for (int32_t i = 0; i < n_iters; ++i) RC_TRY(step_streamed(c, (flags & MLDA_STEP_LOGLIK) != 0));
+        return MLDA_OK;
+    }
     const int32_t timed = std::min(n_iters, kMaxTimedIters);
     while ((int32_t)c->events.size() < timed * 5) {
         hipEvent_t ev;
@@ -601,41 +1090,16 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
         hipEvent_t* ev = slot >= 0 ? &c->events[(size_t)slot * 5] : nullptr;
         if (ev) HIP_TRY(hipEventRecord(ev[0], c->stream));
         uint16_t* z_next = c->z[c->cur ^ 1];
-        if (c->n_tiles > 0) {
-            mlda::SampleArgs a;
-            a.tiles = c->tiles;
-            a.tok_slot = c->tok_slot;
-            a.tok_id = c->tok_id;
-            a.z_cur = c->z[c->cur];
-            a.z_next = z_next;
-            a.slots = c->slots;
-            a.n_wk = c->n_wk;
-            a.n_k = c->n_k;
-            a.K = c->K;
-            a.Kpad = c->Kpad;
-            a.alpha = c->alpha;
-            a.beta = c->beta;
-            a.beta_V = c->beta * (double)c->V;
-            a.seed = c->seed;
-            a.iter = (uint32_t)(c->iter + 1);
-            const int waves = sample_waves_for(c->K);
-            void* kernel_args[] = {&a};
-            HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->packed), dim3((unsigned)c->n_tiles),
-                                    dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds,
-                                    c->stream));
-            rc = launch_check("sample_kernel");
-            if (rc != MLDA_OK) return rc;
-        }
+        RC_TRY(launch_sampler(c, c->z[c->cur], z_next));
         if (ev) HIP_TRY(hipEventRecord(ev[1], c->stream));
-        rc = rebuild_counts(c, z_next, ev ? &ev[2] : nullptr, ev ? &ev[3] : nullptr);
-        if (rc != MLDA_OK) return rc;
+        RC_TRY(rebuild_phi(c, z_next, 0));
+        if (ev) HIP_TRY(hipEventRecord(ev[2], c->stream));
+        RC_TRY(rebuild_theta(c, z_next));
+        if (ev) HIP_TRY(hipEventRecord(ev[3], c->stream));
         c->cur ^= 1;
         c->iter += 1;
         c->ll_fresh = false;
-        if (flags & MLDA_STEP_LOGLIK) {
-            rc = launch_loglik(c);
-            if (rc != MLDA_OK) return rc;
-        }
+        if (flags & MLDA_STEP_LOGLIK) RC_TRY(launch_loglik(c));
         if (ev) HIP_TRY(hipEventRecord(ev[4], c->stream));
     }
     return MLDA_OK;
@@ -648,10 +1112,14 @@ int mlda_iteration(const mlda_ctx* c, int32_t* iter) {
 }
 
 int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
-    if (c->T == 0) return MLDA_OK;
+    RC_TRY(need_state(c));
+    if (c->T_all == 0) return MLDA_OK;
     if (!z) return fail(MLDA_EINVAL, "z is null");
+    if (c->streamed) {
+        HIP_TRY(hipStreamSynchronize(c->stream));
+        std::memcpy(z, c->z_host, (size_t)c->T_all * 2);
+        return MLDA_OK;
+    }
     uint16_t* tmp = c->z[c->cur ^ 1];      // free between steps
     hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
                        c->z[c->cur], c->doc_map, tmp, c->T);
@@ -661,89 +1129,76 @@ int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
 }
 
 int mlda_get_word_topic(mlda_ctx* c, int32_t* n_wk) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!n_wk) return fail(MLDA_EINVAL, "n_wk is null");
-    HIP_TRY(hipMemcpyAsync(n_wk, c->n_wk, (size_t)c->V * c->K * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(n_wk, c->n_wk[c->model_cur], (size_t)c->V * c->K * 4, hipMemcpyDeviceToHost,
+                           c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return MLDA_OK;
 }
 
 int mlda_get_topic_totals(mlda_ctx* c, int32_t* n_k) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!n_k) return fail(MLDA_EINVAL, "n_k is null");
-    HIP_TRY(hipMemcpyAsync(n_k, c->n_k, (size_t)c->K * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(hipStreamSynchronize(c->stream));
-    return MLDA_OK;
-}
-
-static int fetch_row_rec(mlda_ctx* c, std::vector<uint2>& rec) {
-    try { rec.resize((size_t)c->D); } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
-    if (c->D > 0)
-        HIP_TRY(hipMemcpyAsync(rec.data(), c->row_rec, (size_t)c->D * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(n_k, c->n_k[c->model_cur], (size_t)c->K * 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return MLDA_OK;
 }
 
 int mlda_get_doc_topic_nnz(mlda_ctx* c, int64_t* nnz) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!nnz) return fail(MLDA_EINVAL, "nnz is null");
-    std::vector<uint2> rec;
-    rc = fetch_row_rec(c, rec);
-    if (rc != MLDA_OK) return rc;
     int64_t n = 0;
-    for (const uint2& r : rec) n += r.y;
+    std::vector<uint2> rec;
+    if (c->streamed) {
+        RC_TRY(for_each_chunk_rows(c, [&](const HostChunk&) {
+            RC_TRY(fetch_row_rec(c, rec));
+            for (const uint2& r : rec) n += r.y;
+            return (int)MLDA_OK;
+        }));
+    } else {
+        RC_TRY(fetch_row_rec(c, rec));
+        for (const uint2& r : rec) n += r.y;
+    }
     *nnz = n;
     return MLDA_OK;
 }
 
 int mlda_get_doc_topic_csr(mlda_ctx* c, int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!row_ptr) return fail(MLDA_EINVAL, "row_ptr is null");
     std::vector<uint2> rec;
-    rc = fetch_row_rec(c, rec);
-    if (rc != MLDA_OK) return rc;
     std::vector<unsigned char> slots;
-    try { slots.resize(c->slots_bytes); } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
-    if (c->slots_bytes > 0)
-        HIP_TRY(hipMemcpy(slots.data(), c->slots, c->slots_bytes, hipMemcpyDeviceToHost));
     row_ptr[0] = 0;
-    for (int64_t d = 0; d < c->D; ++d) row_ptr[d + 1] = row_ptr[d] + rec[d].y;
-    if (row_ptr[c->D] > 0 && (!topics || !counts)) return fail(MLDA_EINVAL, "topics or counts is null");
-    for (int64_t d = 0; d < c->D; ++d) {
-        const uint32_t nnz = rec[d].y, pad = (nnz + 3u) & ~3u;
-        const unsigned char* base = slots.data() + (size_t)rec[d].x * 16 + mlda::kRowHeader;
-        if (nnz == 0) continue;
-        if (c->packed) {
-            const uint32_t* ent = reinterpret_cast<const uint32_t*>(base);
-            for (uint32_t j = 0; j < nnz; ++j) {
-                counts[row_ptr[d] + j] = (int32_t)(ent[j] >> 18);
-                topics[row_ptr[d] + j] = (uint16_t)((ent[j] >> 2) & 0xffffu);
-            }
-        } else {
-            std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
-            std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
-        }
+    auto take_rows = [&](const HostChunk& h) {
+        RC_TRY(fetch_rows(c, rec, slots));
+        int64_t* ptr = row_ptr + h.d_begin;
+        for (int64_t d = 0; d < c->D; ++d) ptr[d + 1] = ptr[d] + rec[(size_t)d].y;
+        if (ptr[c->D] > ptr[0] && (!topics || !counts)) return fail(MLDA_EINVAL, "topics or counts is null");
+        unpack_rows(c, rec, slots, ptr, topics, counts);
+        return (int)MLDA_OK;
+    };
+    if (c->streamed) {
+        // chunks are visited in document order, so every chunk finds its first row start in place
+        RC_TRY(for_each_chunk_rows(c, take_rows));
+    } else {
+        RC_TRY(take_rows(c->chunks[0]));
     }
     return MLDA_OK;
 }
 
 int mlda_get_loglik(mlda_ctx* c, double* ll) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!ll) return fail(MLDA_EINVAL, "ll is null");
     if (!c->ll_fresh) {
-        rc = launch_loglik(c);
-        if (rc != MLDA_OK) return rc;
+        if (c->streamed) {
+            RC_TRY(for_each_chunk_rows(c, [](const HostChunk&) { return (int)MLDA_OK; }));
+            RC_TRY(finish_loglik_streamed(c));
+        } else {
+            RC_TRY(launch_loglik(c));
+        }
     }
-    HIP_TRY(hipMemcpyAsync(ll, c->ll_value, 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(ll, c->ll_scalars, 8, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return MLDA_OK;
 }
@@ -766,8 +1221,7 @@ int mlda_get_timing(mlda_ctx* c, double* ms, int32_t capacity_iters, int32_t* n_
 }
 
 int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, int32_t* n_iters) {
-    int rc = need_state(c);
-    if (rc != MLDA_OK) return rc;
+    RC_TRY(need_state(c));
     if (!bytes || !n_iters || capacity_iters < 0) return fail(MLDA_EINVAL, "bad argument");
     const int32_t n = std::min({c->last_step_iters, capacity_iters, kMaxTimedIters});
     // iteration j of the step (0-based, of last_step_iters) sampled from the state left by
@@ -788,12 +1242,7 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
     return MLDA_OK;
 }
 
-void mlda_destroy(mlda_ctx* c) {
-    if (!c) return;
-    (void)hipStreamSynchronize(c->stream);
-    for (hipEvent_t ev : c->events) (void)hipEventDestroy(ev);
-    delete c;
-}
+void mlda_destroy(mlda_ctx* c) { destroy(c); }
 
 int mlda_philox_uniform(uint64_t seed, uint32_t iter, uint64_t token0, int64_t n, double* out_dev,
                         void* hip_stream) {

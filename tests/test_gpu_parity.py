@@ -189,6 +189,78 @@ def test_empty_documents_and_unused_words(mlda):
     model.close()
 
 
+@pytest.mark.parametrize("chunks", [2, 3, 7])
+def test_streamed_chunks_match_oracle(mlda, chunks):
+    """The corpus cut into chunks that take turns on the GPU (Algorithm 1, WorkSchedule2) gives
+    the oracle's results like the resident corpus does."""
+    c = corpus_synth.generate("C1")
+    cfg = c.config
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, chunks=chunks)
+    model.init_random()
+    z = oracle.init_topics(c.T, cfg.K, SEED)
+    assert np.array_equal(model.assignments(), z)
+    check_counts(model, c, z, cfg.V, cfg.K)
+    for it in (1, 2, 3):
+        say("streamed", chunks, "iteration", it)
+        z = check_step(model, c, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, it)
+    # the log-likelihood evaluated inside the step, and two iterations in one call
+    model.step(2, loglik=True)
+    for it in (4, 5):
+        n_wk, n_k = oracle.count_word_topic(c.word_ids, z, cfg.V, cfg.K)
+        z = oracle.iteration(c.doc_ptr, c.word_ids, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, it, n_wk, n_k)
+    assert model.iteration == 5 and np.array_equal(model.assignments(), z)
+    n_wk, n_k = check_counts(model, c, z, cfg.V, cfg.K)
+    ll = oracle.loglik(c.doc_ptr, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
+    assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
+    assert len(model.timing()) == 0           # per-kernel times are not kept for streamed chunks
+    model.close()
+
+
+def test_streamed_edge_cases(mlda):
+    """More chunks than documents, empty documents, long rows in 6-byte entries, and a saved
+    state carried from a resident context into a streamed one."""
+    base = corpus_synth.tiny(D=5, V=30, K=9, mean_len=12, seed=3)
+    lens = np.diff(base.doc_ptr)
+    new_lens = np.zeros(2 * len(lens) + 1, dtype=np.int64)
+    new_lens[1::2] = lens                                   # empty documents in between
+
+    class C:  # minimal corpus record
+        pass
+    c = C(); c.doc_ptr = np.concatenate([[0], np.cumsum(new_lens)]).astype(np.int64)
+    c.word_ids = base.word_ids; c.T = base.T
+    V, K, alpha, beta = 30, 9, 0.4, 0.02
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, 11, chunks=16)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, 11)
+    for it in (1, 2):
+        z = check_step(model, c, z, V, K, alpha, beta, 11, it)
+    model.close()
+
+    big = corpus_synth.tiny(D=4, V=40, K=50, mean_len=16500, seed=8)      # 6-byte theta entries
+    model = mlda.Mlda(big.doc_ptr, big.word_ids, 40, 50, 1.0, 0.01, SEED, chunks=3)
+    model.init_random()
+    z = oracle.init_topics(big.T, 50, SEED)
+    z = check_step(model, big, z, 40, 50, 1.0, 0.01, SEED, 1)
+    model.close()
+
+    c1 = corpus_synth.generate("C1")
+    cfg = c1.config
+    args = (c1.doc_ptr, c1.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    a = mlda.Mlda(*args); a.init_random(); a.step(4)
+    r = mlda.Mlda(*args); r.init_random(); r.step(2)
+    s = mlda.Mlda(*args, chunks=4); s.set_assignments(r.assignments(), it=r.iteration); s.step(2)
+    assert np.array_equal(s.assignments(), a.assignments())
+    assert np.array_equal(s.word_topic(), a.word_topic())
+    assert abs(s.loglik() - a.loglik()) <= 1e-9 * abs(a.loglik())
+    for m in (a, r, s):
+        m.close()
+
+    empty = mlda.Mlda(np.zeros(3, dtype=np.int64), np.zeros(0, dtype=np.int32), 4, 3, 0.5, 0.01, 1, chunks=2)
+    empty.init_random(); empty.step(2, loglik=True)
+    assert empty.iteration == 2 and empty.doc_topic_nnz() == 0 and abs(empty.loglik()) < 1e-9
+    empty.close()
+
+
 def test_empty_corpus(mlda):
     doc_ptr = np.zeros(4, dtype=np.int64)
     model = mlda.Mlda(doc_ptr, np.zeros(0, dtype=np.int32), 5, 3, 0.5, 0.01, 1)
