@@ -305,6 +305,26 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     block_partial_store(ll, ll_partial);
 }
 
+// The two per-token index arrays that follow from tok_id and the document records are built
+// on the device rather than sent over PCIe.  doc_map (Section 6.2's document->token map) is the
+// inverse of tok_id; tokens are numbered from `first` inside a chunk.
+__global__ void derive_doc_map_kernel(const int32_t* tok_id, int64_t T, int64_t first, int32_t* doc_map) {
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos < T) doc_map[(int64_t)tok_id[pos] - first] = (int32_t)pos;
+}
+
+// tok_slot[pos] = slot of the theta row of the document that owns word-major token pos.  One
+// wave per document, persistent.
+__global__ __launch_bounds__(kWave) void derive_tok_slot_kernel(const DocRec* docs, int64_t D,
+                                                                const int32_t* doc_map,
+                                                                uint32_t* tok_slot) {
+    const int lane = (int)threadIdx.x;
+    for (int64_t i = blockIdx.x; i < D; i += gridDim.x) {
+        const DocRec r = docs[i];
+        for (int j = lane; j < r.n; j += kWave) tok_slot[doc_map[r.begin + j]] = r.slot;
+    }
+}
+
 // Boundary order changes.  doc_map[t] = word-major position of document-major token t;
 // tok_id[pos] = document-major index of word-major position pos.
 __global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,

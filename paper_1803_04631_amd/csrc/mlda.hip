@@ -78,7 +78,8 @@ constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entri
 
 // Where the buffers of one chunk of documents lie inside its part of the workspace (byte
 // offsets).  The static part (up to static_bytes) is the preprocessed corpus and is copied
-// from the host as one block; z and the theta rows follow.
+// from the host as one block; two index arrays derived from it on the device, z and the theta
+// rows follow.
 struct ChunkLayout {
     size_t tok_slot = 0, tok_id = 0, doc_map = 0, doc_ptr = 0, doc_order = 0, row_rec = 0, tiles = 0,
            segs = 0, split = 0, static_bytes = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
@@ -89,9 +90,7 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
     ChunkLayout L;
     size_t at = 0;
     auto put = [&](size_t bytes) { const size_t o = at; at += align_up(bytes, kAlign); return o; };
-    L.tok_slot = put((size_t)T * 4);
     L.tok_id = put((size_t)T * 4);
-    L.doc_map = put((size_t)T * 4);
     L.doc_ptr = put((size_t)(D + 1) * 4);
     L.doc_order = put((size_t)D * sizeof(mlda::DocRec));
     L.row_rec = put((size_t)D * 8);
@@ -99,6 +98,8 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
     L.segs = put(n_segs * sizeof(mlda::Tile));
     L.split = put(n_split * 4);
     L.static_bytes = at;
+    L.tok_slot = put((size_t)T * 4);       // derived on the device from the static part
+    L.doc_map = put((size_t)T * 4);
     L.z0 = put((size_t)T * 2);
     L.z1 = put((size_t)T * 2);
     L.slots = put(slots_bytes);
@@ -281,9 +282,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         h.arena = (unsigned char*)std::malloc(std::max<size_t>(h.L.static_bytes, 1));
         if (!h.arena) return fail(MLDA_ENOMEM, "out of host memory");
     }
-    uint32_t* tok_slot = (uint32_t*)(h.arena + h.L.tok_slot);
     int32_t* tok_id = (int32_t*)(h.arena + h.L.tok_id);
-    int32_t* doc_map = (int32_t*)(h.arena + h.L.doc_map);
     int32_t* doc_ptr32 = (int32_t*)(h.arena + h.L.doc_ptr);
     mlda::DocRec* doc_recs = (mlda::DocRec*)(h.arena + h.L.doc_order);
     uint2* row_rec = (uint2*)(h.arena + h.L.row_rec);
@@ -291,16 +290,27 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
     mlda::Tile* segs = (mlda::Tile*)(h.arena + h.L.segs);
     int32_t* split_words = (int32_t*)(h.arena + h.L.split);
 
+    // (the slot of every tile's first document orders the tiles below)
+    std::vector<uint32_t> tile_key;
+    std::vector<int32_t> tile_base;
+    try {
+        tile_key.resize(n_tiles);
+        tile_base.resize((size_t)V + 1);
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    tile_base[0] = 0;
+    for (int32_t v = 0; v < V; ++v)
+        tile_base[v + 1] = tile_base[v] + (word_ptr[v + 1] - word_ptr[v] + tile - 1) / tile;
     parallel_chunks(n_parts, [&](int p) {
         auto& start = part_hist[p];
         for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
             const int64_t d = doc_order[(size_t)i];
             for (int64_t t = start_of(d); t < start_of(d) + len_of(d); ++t) {
                 const int32_t w = word_ids[t];
-                const int32_t pos = word_ptr[w] + start[w]++;
-                tok_id[pos] = (int32_t)(tok_begin + t);     // the caller's token index keys the uniforms
-                tok_slot[pos] = slot_of[(size_t)d];
-                doc_map[t] = pos;
+                const int32_t in_word = start[w]++;
+                tok_id[word_ptr[w] + in_word] = (int32_t)(tok_begin + t);   // the caller's token index keys the uniforms
+                if (in_word % tile == 0) tile_key[(size_t)(tile_base[w] + in_word / tile)] = slot_of[(size_t)d];
             }
         }
     });
@@ -317,8 +327,9 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
     size_t it = 0, is = 0, ip = 0;
     for (int32_t v = 0; v < V; ++v) {
         const int32_t n = word_ptr[v + 1] - word_ptr[v];
-        for (int32_t b = 0; b < n; b += tile)
-            tiles[it++] = mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), n <= tile ? 1 : 0};
+        // `whole` carries the tile's index until the tiles are sorted
+        for (int32_t b = 0; b < n; b += tile, ++it)
+            tiles[it] = mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), (int32_t)it};
         if (!accumulate && n > kPhiSegment) split_words[ip++] = v;
         for (int32_t b = 0; b < n; b += kPhiSegment)
             segs[is++] = mlda::Tile{v, word_ptr[v] + b, std::min(kPhiSegment, n - b),
@@ -332,8 +343,12 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         // of heavy words first, Section 6.1.2; here the long-row tiles come first, which also
         // keeps the tail short.)
         std::stable_sort(tiles, tiles + n_tiles, [&](const mlda::Tile& a, const mlda::Tile& b) {
-            return tok_slot[(size_t)a.begin] < tok_slot[(size_t)b.begin];
+            return tile_key[(size_t)a.whole] < tile_key[(size_t)b.whole];
         });
+        for (size_t i = 0; i < n_tiles; ++i) {
+            const int32_t n = word_ptr[tiles[i].word + 1] - word_ptr[tiles[i].word];
+            tiles[i].whole = n <= tile ? 1 : 0;
+        }
         std::stable_sort(segs, segs + n_segs,
                          [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
     } catch (const std::bad_alloc&) {
@@ -380,7 +395,9 @@ struct mlda_ctx {
     bool streamed = false;
     unsigned char* slot_base[2] = {nullptr, nullptr};   // the workspace parts chunks are attached to
     uint16_t* z_host = nullptr;          // streamed: all assignments in the caller's order (pinned)
-    hipStream_t copy_stream = nullptr;   // streamed: uploads run beside the kernels
+    hipStream_t copy_stream = nullptr;   // streamed: uploads run beside the kernels,
+    hipStream_t down_stream = nullptr;   // and so do the downloads of new assignments
+    hipEvent_t z_ready = nullptr;        // the attached chunk's assignments are in document order
     hipEvent_t slot_ready[2] = {nullptr, nullptr}, slot_free[2] = {nullptr, nullptr};
     std::vector<hipEvent_t> z_stored;    // per chunk: its assignments have reached z_host
     int64_t visits = 0;                  // chunk visits so far (picks the slot)
@@ -441,9 +458,18 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->theta_grid = (int32_t)std::min<int64_t>({h.D, (int64_t)c->n_cus * per_cu, (int64_t)kMaxThetaGrid});
 }
 
-// What a lane of the sampler reads when it has no entries of its own: four padding entries
-// (count 0, topic K) at the start of the slot buffer.
-void write_padding_entries(mlda_ctx* c) {
+// After the static part of a chunk has arrived: the index arrays that follow from it
+// (document->token map, slot of every token's theta row), and what a lane of the sampler
+// reads when it has no entries of its own: four padding entries (count 0, topic K) at the
+// start of the slot buffer.
+void derive_chunk_arrays(mlda_ctx* c) {
+    if (c->T > 0) {
+        hipLaunchKernelGGL(mlda::derive_doc_map_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
+                           c->tok_id, c->T, c->at->tok_begin, c->doc_map);
+        const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * 32);
+        hipLaunchKernelGGL(mlda::derive_tok_slot_kernel, dim3((unsigned)grid), dim3(mlda::kWave), 0, c->stream,
+                           c->doc_order, c->D, c->doc_map, c->tok_slot);
+    }
     hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(1), dim3(256), 0, c->stream, (int32_t*)c->slots,
                        (int64_t)4, (int32_t)((uint32_t)c->K << 2));
 }
@@ -469,7 +495,7 @@ int attach(mlda_ctx* c, int32_t m, bool with_z) {
     }
     HIP_TRY(hipEventRecord(c->slot_ready[s], c->copy_stream));
     HIP_TRY(hipStreamWaitEvent(c->stream, c->slot_ready[s], 0));
-    write_padding_entries(c);
+    derive_chunk_arrays(c);
     if (with_z && h.T > 0)
         hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
                            c->z[1], c->tok_id, c->z[0], h.T, h.tok_begin);
@@ -485,12 +511,18 @@ int store_z_and_release(mlda_ctx* c, int32_t m, const uint16_t* z_word, bool sto
         uint16_t* tmp = (z_word == c->z[0]) ? c->z[1] : c->z[0];
         hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
                            z_word, c->doc_map, tmp, h.T);
+        RC_TRY(launch_check("to_doc_major_kernel"));
+        // the download runs on its own stream, beside the next chunk's kernels and upload
+        HIP_TRY(hipEventRecord(c->z_ready, c->stream));
+        HIP_TRY(hipStreamWaitEvent(c->down_stream, c->z_ready, 0));
         HIP_TRY(hipMemcpyAsync(c->z_host + h.tok_begin, tmp, (size_t)h.T * 2, hipMemcpyDeviceToHost,
-                               c->stream));
-        HIP_TRY(hipEventRecord(c->z_stored[(size_t)m], c->stream));
+                               c->down_stream));
+        HIP_TRY(hipEventRecord(c->z_stored[(size_t)m], c->down_stream));
+        HIP_TRY(hipEventRecord(c->slot_free[s], c->down_stream));
+    } else {
+        HIP_TRY(hipEventRecord(c->slot_free[s], c->stream));
     }
-    HIP_TRY(hipEventRecord(c->slot_free[s], c->stream));
-    return launch_check("storing a chunk's assignments");
+    return MLDA_OK;
 }
 
 // phi (into n_wk[which]) from the attached chunk's assignments z (word-major).  One chunk:
@@ -742,10 +774,12 @@ int device_limits(mlda_ctx* c) {
 void destroy(mlda_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
-    if (c->copy_stream) {
-        (void)hipStreamSynchronize(c->copy_stream);
-        (void)hipStreamDestroy(c->copy_stream);
-    }
+    for (hipStream_t extra : {c->copy_stream, c->down_stream})
+        if (extra) {
+            (void)hipStreamSynchronize(extra);
+            (void)hipStreamDestroy(extra);
+        }
+    if (c->z_ready) (void)hipEventDestroy(c->z_ready);
     for (hipEvent_t ev : c->events) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : c->z_stored) (void)hipEventDestroy(ev);
     for (int s = 0; s < 2; ++s) {
@@ -907,7 +941,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         if (h.L.static_bytes > 0)
             e = hipMemcpyAsync(c->slot_base[0], h.arena, h.L.static_bytes, hipMemcpyHostToDevice, c->stream);
         if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
-        if (rc == MLDA_OK) { write_padding_entries(c); rc = finish_create(c, base, ML); }
+        if (rc == MLDA_OK) { derive_chunk_arrays(c); rc = finish_create(c, base, ML); }
         if (rc == MLDA_OK) {
             e = hipStreamSynchronize(c->stream);
             if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
@@ -964,6 +998,8 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
         c->z_host = (uint16_t*)zh;
         // every stream at the default priority
         hip_ok(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        hip_ok(hipStreamCreateWithFlags(&c->down_stream, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        hip_ok(hipEventCreateWithFlags(&c->z_ready, hipEventDisableTiming), "hipEventCreateWithFlags");
         for (int s = 0; s < 2; ++s) {
             hip_ok(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming), "hipEventCreateWithFlags");
             hip_ok(hipEventCreateWithFlags(&c->slot_free[s], hipEventDisableTiming), "hipEventCreateWithFlags");
@@ -1015,6 +1051,7 @@ int mlda_set_assignments(mlda_ctx* c, const uint16_t* z, int32_t iter) {
     if (c->streamed) {
         HIP_TRY(hipStreamSynchronize(c->stream));
         HIP_TRY(hipStreamSynchronize(c->copy_stream));
+        HIP_TRY(hipStreamSynchronize(c->down_stream));
         if (c->T_all > 0) std::memcpy(c->z_host, z, (size_t)c->T_all * 2);
         RC_TRY(rebuild_model_streamed(c, false));
     } else {
@@ -1117,6 +1154,7 @@ int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
     if (!z) return fail(MLDA_EINVAL, "z is null");
     if (c->streamed) {
         HIP_TRY(hipStreamSynchronize(c->stream));
+        HIP_TRY(hipStreamSynchronize(c->down_stream));
         std::memcpy(z, c->z_host, (size_t)c->T_all * 2);
         return MLDA_OK;
     }
