@@ -154,9 +154,9 @@ __host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool packed) {
 // dense row lives in LDS and is left all-zero for the next document.  Documents are taken in
 // the order the tokens have inside a word (falling length), so that documents in flight
 // together gather from neighbouring lines of z.  The walk is a chain of dependent loads
-// (record -> map -> z), so it is software-pipelined: while the current document's topics are
-// gathered, the map entries of the wave's next document and the record of the one after are
-// already on their way.  Rows are written in the layout the sampler reads (SplitRows or
+// (record -> map -> z), so it is software-pipelined: while the current document is counted,
+// the topics of the wave's next document, the map entries of the one after and the record
+// after that are already on their way.  Rows are written in the layout the sampler reads (SplitRows or
 // PackedRows, see kernels_sample.hpp); padding entries hold count 0 and topic K.
 // With PackedRows the compaction visits only the 32-topic groups that hold a non-zero bin
 // (one mark bit per topic), so its cost follows the row's length rather than K.
@@ -212,18 +212,28 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     int64_t i = (int)blockIdx.x < per_xcd * kXcds
                     ? (int64_t)((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds
                     : (int64_t)blockIdx.x;
+    // Three loads deep: the topics of this document's first 128 tokens have been gathered, the
+    // positions of the next document's tokens read, and the record after that fetched.
     DocRec cur = i < D ? docs[i] : none;
     DocRec nxt = i + step < D ? docs[i + step] : none;
-    int p0 = doc_token_position(doc_map, cur, lane);
-    int p1 = doc_token_position(doc_map, cur, lane + kWave);
+    DocRec after = i + 2 * step < D ? docs[i + 2 * step] : none;
+    int k0, k1;
+    {
+        const int c0 = doc_token_position(doc_map, cur, lane);
+        const int c1 = doc_token_position(doc_map, cur, lane + kWave);
+        k0 = c0 >= 0 ? (int)z[c0] : -1;
+        k1 = c1 >= 0 ? (int)z[c1] : -1;
+    }
+    int p0 = doc_token_position(doc_map, nxt, lane);
+    int p1 = doc_token_position(doc_map, nxt, lane + kWave);
     for (; i < D; i += step) {
-        // topics of the current document's first 128 tokens
-        const int k0 = p0 >= 0 ? (int)z[p0] : -1;
-        const int k1 = p1 >= 0 ? (int)z[p1] : -1;
-        // on their way meanwhile: the next document's positions, the record after it
-        const int q0 = doc_token_position(doc_map, nxt, lane);
-        const int q1 = doc_token_position(doc_map, nxt, lane + kWave);
-        const DocRec after = i + 2 * step < D ? docs[i + 2 * step] : none;
+        // on their way while this document is counted: the next document's topics, the
+        // positions of the one after, the record after that
+        const int n0 = p0 >= 0 ? (int)z[p0] : -1;
+        const int n1 = p1 >= 0 ? (int)z[p1] : -1;
+        const int q0 = doc_token_position(doc_map, after, lane);
+        const int q1 = doc_token_position(doc_map, after, lane + kWave);
+        const DocRec later = i + 3 * step < D ? docs[i + 3 * step] : none;
 
         int fresh = 0;                    // first token of a topic
         if (k0 >= 0) fresh += count_topic(k0);
@@ -298,7 +308,7 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         }
         visited += (unsigned long long)cur.n * (unsigned long long)nnz;
         __syncthreads();
-        cur = nxt; nxt = after; p0 = q0; p1 = q1;
+        cur = nxt; nxt = after; after = later; k0 = n0; k1 = n1; p0 = q0; p1 = q1;
     }
     // row entries the next sampling pass will read: one row walk per token
     if (lane == 0 && visited != 0) atomicAdd(row_entries, visited);
