@@ -468,14 +468,16 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         const int n_here = min(kWave, tl.count - b * kWave);
         // Shapes of a pass (lanes per token, quads per lane -> entries per row at most):
         //   0 (4,1) 16   1 (4,2) 32   2 (8,2) 64   3 (8,3) 96   4 (16,2) 128   5 (16,3) 192
-        //   6 (32,3) 384   7 (64,3) 768   8 = one longer row, walked twice by the wave
+        //   6 (32,2) 256   7 (32,3) 384   8 (64,2) 512   9 (64,3) 768
+        //   10 = one longer row, walked twice by the wave
         // Which tokens of the batch have rows beyond each of these lengths (lanes past the
         // batch's end hold nnz = 0): the shape of every pass follows from these masks.
         static_assert(kKeptQuads == 3, "the pass shapes assume three kept quads per lane");
         const uint64_t over16 = __ballot(mine.nnz > 16), over32 = __ballot(mine.nnz > 32);
         const uint64_t over64 = __ballot(mine.nnz > 64), over96 = __ballot(mine.nnz > 96);
         const uint64_t over128 = __ballot(mine.nnz > 128), over192 = __ballot(mine.nnz > 192);
-        const uint64_t over384 = __ballot(mine.nnz > 384), over768 = __ballot(mine.nnz > 768);
+        const uint64_t over256 = __ballot(mine.nnz > 256), over384 = __ballot(mine.nnz > 384);
+        const uint64_t over512 = __ballot(mine.nnz > 512), over768 = __ballot(mine.nnz > 768);
         auto any = [](uint64_t mask, int t0, uint32_t window) {      // 1 if a token of the window is set
             const uint32_t w = (uint32_t)(mask >> t0) & window;
             return (int)((w | (0u - w)) >> 31);
@@ -484,11 +486,12 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             if (!any(over32, t0, 0xffffu)) return any(over16, t0, 0xffffu);
             if (!any(over96, t0, 0xffu)) return 2 + any(over64, t0, 0xffu);
             if (!any(over192, t0, 0xfu)) return 4 + any(over128, t0, 0xfu);
-            if (!any(over384, t0, 0x3u)) return 6;
-            return 7 + any(over768, t0, 0x1u);
+            if (!any(over384, t0, 0x3u)) return 6 + any(over256, t0, 0x3u);
+            if (!any(over768, t0, 0x1u)) return 8 + any(over512, t0, 0x1u);
+            return 10;
         };
-        auto lanes_log2 = [](int shape) { return (int)((0x665443322ull >> (4 * shape)) & 0xfull); };
-        auto quads_of = [](int shape) { return (int)((0x033323221ull >> (4 * shape)) & 0xfull); };
+        auto lanes_log2 = [](int shape) { return (int)((0x66655443322ull >> (4 * shape)) & 0xfull); };
+        auto quads_of = [](int shape) { return (int)((0x03232323221ull >> (4 * shape)) & 0xfull); };
         // where a pass's rows are, and the loads of the quads its lanes keep.  `rec` is the
         // record of the lane's token, `sl` the lane's place inside its group.  A pass that
         // would run past the batch's 64 records works on the last one several times over.
@@ -531,8 +534,10 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             case 3: row_pass_kept<Layout, 8, 3>(rec, sl, mine_raw, pstar, lane); break;
             case 4: row_pass_kept<Layout, 16, 2>(rec, sl, mine_raw, pstar, lane); break;
             case 5: row_pass_kept<Layout, 16, 3>(rec, sl, mine_raw, pstar, lane); break;
-            case 6: row_pass_kept<Layout, 32, 3>(rec, sl, mine_raw, pstar, lane); break;
-            case 7: row_pass_kept<Layout, 64, 3>(rec, sl, mine_raw, pstar, lane); break;
+            case 6: row_pass_kept<Layout, 32, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 7: row_pass_kept<Layout, 32, 3>(rec, sl, mine_raw, pstar, lane); break;
+            case 8: row_pass_kept<Layout, 64, 2>(rec, sl, mine_raw, pstar, lane); break;
+            case 9: row_pass_kept<Layout, 64, 3>(rec, sl, mine_raw, pstar, lane); break;
             default: row_pass_long<Layout>(a.slots, rec, K, pstar, lane); break;
             }
         };
