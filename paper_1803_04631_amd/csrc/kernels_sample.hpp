@@ -165,6 +165,7 @@ __device__ __forceinline__ int group_last_lane(int lane) {
 // uint16 topics[round4(nnz)].  Always usable.
 struct SplitRows {
     static constexpr int kEntryBytes = 6;
+    static constexpr int kWavesPerSimd = 5;
     struct Raw {            // four consecutive entries as they come from memory
         int4 c;             // counts
         uint2 t;            // topics, two per dword
@@ -205,6 +206,7 @@ struct SplitRows {
 // low 18 bits are the topic's key.  Usable when no document has 16384 tokens or more.
 struct PackedRows {
     static constexpr int kEntryBytes = 4;
+    static constexpr int kWavesPerSimd = 6;
     static constexpr int kMaxCount = (1 << 14) - 1;
     struct Raw {
         uint4 e;
@@ -384,9 +386,10 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenR
 }
 
 template <int kWaves, class Layout>
-// Five waves per SIMD (96 VGPRs): three kept quads per lane and the next pass's loads need
-// the registers; the walk hides HBM latency by occupancy as well as by those early loads.
-__attribute__((amdgpu_waves_per_eu(5)))
+// Six waves per SIMD (80 VGPRs) with 4-byte entries, five (96 VGPRs) with 6-byte entries,
+// whose quads take half as many registers again: the walk hides HBM latency by occupancy as
+// well as by the early loads.
+__attribute__((amdgpu_waves_per_eu(Layout::kWavesPerSimd)))
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int kGroup = dense_group(kWaves);
@@ -552,12 +555,18 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // ---- one token per lane again: dense bucket, store
-        if (valid) {
-            int z_new = (int)my_rec[lane].off;
-            if (z_new < 0)
-                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, my_rec[lane].u, mine.o, mine.w_o,
-                                            delta);
-            a.z_next[pos] = (uint16_t)z_new;
+        // (the token's topic and corrected weight are read back from its record rather than
+        // kept in registers across the passes)
+        if (b * kWave + lane < tl.count) {
+            const TokenRec* rec = &my_rec[lane];
+            int z_new = (int)rec->off;
+            if (z_new < 0) {
+                const int o = rec->o;
+                const float w_o = rec->w_o;
+                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, o, w_o,
+                                                    (double)w_o - (double)pstar[o]);
+            }
+            a.z_next[tl.begin + b * kWave + lane] = (uint16_t)z_new;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
