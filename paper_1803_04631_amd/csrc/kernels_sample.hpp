@@ -57,7 +57,7 @@ struct SampleArgs {
 
 constexpr int kRowHeader = 16;  // bytes before a theta row's entries
 // Topics per fp64 prefix group of the dense bucket: 4 where LDS has room (workgroups of four
-// waves, K <= 2048), 16 for the large-K workgroups of sixteen waves.
+// waves, K <= 2048), 16 for the large-K workgroups of twelve waves.
 __host__ __device__ constexpr int dense_group(int waves) { return waves == 4 ? 4 : 16; }
 constexpr int kKeptQuads = 3;   // quads (of four entries) a lane keeps in registers at most
 

@@ -50,14 +50,15 @@ int fail(int code, const std::string& msg) {
 constexpr size_t kAlign = 256;        // workspace sub-buffer alignment
 constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
 // waves per sampling workgroup: more of them share one staged p* column when K is large
-int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 16; }
+// (twelve: two such workgroups fill a CU's six waves per SIMD, and their LDS fits twice)
+int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 12; }
 
 const void* sample_kernel_for(int32_t K, bool packed) {
     if (sample_waves_for(K) == 4)
         return packed ? (const void*)mlda::sample_kernel<4, mlda::PackedRows>
                       : (const void*)mlda::sample_kernel<4, mlda::SplitRows>;
-    return packed ? (const void*)mlda::sample_kernel<16, mlda::PackedRows>
-                  : (const void*)mlda::sample_kernel<16, mlda::SplitRows>;
+    return packed ? (const void*)mlda::sample_kernel<12, mlda::PackedRows>
+                  : (const void*)mlda::sample_kernel<12, mlda::SplitRows>;
 }
 constexpr int kMaxTimedIters = 1024;
 
