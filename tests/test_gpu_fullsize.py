@@ -108,3 +108,34 @@ def test_first_iteration_at_full_size(name, n_listed):
     assert abs(model.loglik() - ll) <= 1e-5 * abs(ll)
     say(name, "log-likelihood agrees")
     model.close()
+
+
+def test_streamed_chunks_at_full_size():
+    """C3 cut into three chunks that take turns on the GPU gives, bit for bit, the state the
+    resident corpus reaches after two iterations (token indices beyond a chunk's own range,
+    chunk boundaries inside the 32-bit position arithmetic, 10^8 tokens through pinned memory)."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    import paper_1803_04631_amd as mlda
+    cfg = corpus_synth.CONFIGS["C3"]
+    c = corpus_synth.generate(cfg)
+    args = (c.doc_ptr, c.word_ids, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED)
+    resident = mlda.Mlda(*args)
+    resident.init_random()
+    resident.step(2, loglik=True)
+    z, n_k, ll, nnz = resident.assignments(), resident.topic_totals(), resident.loglik(), resident.doc_topic_nnz()
+    resident.close()
+    del resident
+    torch.cuda.empty_cache()
+    say("C3 resident run done")
+    streamed = mlda.Mlda(*args, chunks=3)
+    streamed.init_random()
+    streamed.step(2, loglik=True)
+    assert streamed.iteration == 2
+    assert np.array_equal(streamed.assignments(), z)
+    assert np.array_equal(streamed.topic_totals(), n_k)
+    assert abs(streamed.loglik() - ll) <= 1e-9 * abs(ll)
+    assert streamed.doc_topic_nnz() == nnz
+    say("C3 streamed run agrees")
+    streamed.close()
