@@ -432,7 +432,6 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         }
     }
     __syncthreads();
-    const double W = cp[ng - 1];           // sum_k p*(k);  Q = alpha W (Eq. 7)
 
     // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
     // place inside its group, its first entry
@@ -458,7 +457,8 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             mine.w_o = (float)(((double)(phi_v[mine.o] - 1) + a.beta) /
                                ((double)(a.n_k[mine.o] - 1) + a.beta_V));
             delta = (double)mine.w_o - (double)pstar[mine.o];
-            mine.Qp = a.alpha * (W + delta);
+            // cp[ng - 1] = sum_k p*(k), read from LDS where it is needed; Q = alpha sum (Eq. 7)
+            mine.Qp = a.alpha * (cp[ng - 1] + delta);
         }
         my_rec[lane] = mine;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
