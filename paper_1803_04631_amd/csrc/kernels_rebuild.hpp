@@ -131,9 +131,12 @@ struct __align__(16) DocRec {
     int32_t doc;        // document id
 };
 
-// Word-major position of the document's token `j`, or -1 past its end.
+// Where the topic of the document's token `j` is found in z, or -1 past the document's end:
+// its word-major position, through the map; or, without a map (z in document order), the
+// token's own index.
 __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const DocRec& r, int j) {
-    return j < r.n ? doc_map[r.begin + j] : -1;
+    if (j >= r.n) return -1;
+    return doc_map ? doc_map[r.begin + j] : r.begin + j;
 }
 
 // LDS bytes of the rebuild's dense row.  Rows with 4-byte entries hold counts below 2^14:
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         if (k0 >= 0) fresh += count_topic(k0);
         if (k1 >= 0) fresh += count_topic(k1);
         for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
-            fresh += count_topic((int)z[doc_map[cur.begin + j]]);
+            fresh += count_topic((int)z[doc_token_position(doc_map, cur, j)]);
         __syncthreads();
         int nnz;
         unsigned char* head = slots + (size_t)cur.slot * 16u;
@@ -335,12 +338,49 @@ __global__ __launch_bounds__(kWave) void derive_tok_slot_kernel(const DocRec* do
     }
 }
 
+// The same without the map, in two steps.  First the document of every 64th token of the
+// chunk is found by bisection of the chunk's doc_ptr (D + 1 entries, tokens numbered from 0
+// inside the chunk): block_doc[b] = the last d with doc_ptr[d] <= 64 b.
+__global__ void derive_block_doc_kernel(const int32_t* doc_ptr, int32_t D, int64_t n_blocks,
+                                        int32_t* block_doc) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_blocks) return;
+    const int32_t t = (int32_t)(b * 64);
+    int lo = 0, hi = D;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (doc_ptr[mid] <= t) lo = mid; else hi = mid;
+    }
+    block_doc[b] = lo;
+}
+
+// Then every word-major token starts at its block's document and walks forward to its own
+// (at most a few documents, unless they are very short).
+__global__ void derive_tok_slot_by_search_kernel(const int32_t* tok_id, int64_t T, int64_t first,
+                                                 const int32_t* doc_ptr, int32_t D,
+                                                 const int32_t* block_doc, const uint2* row_rec,
+                                                 uint32_t* tok_slot) {
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos >= T) return;
+    const int32_t t = (int32_t)((int64_t)tok_id[pos] - first);
+    int d = block_doc[t >> 6];
+    while (d + 1 < D && doc_ptr[d + 1] <= t) ++d;
+    tok_slot[pos] = row_rec[d].x;
+}
+
 // Boundary order changes.  doc_map[t] = word-major position of document-major token t;
 // tok_id[pos] = document-major index of word-major position pos.
 __global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,
                                     uint16_t* z_doc, int64_t T) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < T) z_doc[t] = z_word[doc_map[t]];
+}
+
+// The same order change as a scatter, for when there is no map.
+__global__ void to_doc_major_scatter_kernel(const uint16_t* z_word, const int32_t* tok_id,
+                                            uint16_t* z_doc, int64_t T, int64_t first) {
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos < T) z_doc[(int64_t)tok_id[pos] - first] = z_word[pos];
 }
 
 // (tok_id counts from the start of the whole corpus, z_doc from token `first`: a chunk of

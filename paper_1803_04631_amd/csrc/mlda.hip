@@ -83,7 +83,7 @@ constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entri
 // rows follow.
 struct ChunkLayout {
     size_t tok_slot = 0, tok_id = 0, doc_map = 0, doc_ptr = 0, doc_order = 0, row_rec = 0, tiles = 0,
-           segs = 0, split = 0, static_bytes = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
+           segs = 0, split = 0, static_bytes = 0, block_doc = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
 };
 
 ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tiles, size_t n_segs,
@@ -101,6 +101,7 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
     L.static_bytes = at;
     L.tok_slot = put((size_t)T * 4);       // derived on the device from the static part
     L.doc_map = put((size_t)T * 4);
+    L.block_doc = put(((size_t)T / 64 + 1) * 4);
     L.z0 = put((size_t)T * 2);
     L.z1 = put((size_t)T * 2);
     L.slots = put(slots_bytes);
@@ -407,12 +408,13 @@ struct mlda_ctx {
     const HostChunk* at = nullptr;
     int64_t D = 0, T = 0;
     uint32_t* tok_slot = nullptr;        // [T] slot of the theta row of each word-major token's document
-    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr, *block_doc = nullptr;
     mlda::DocRec* doc_order = nullptr;   // documents by falling length, as the theta rebuild walks them
     int32_t theta_grid = 0;
     bool packed = false;
     int32_t* split_words = nullptr;
     uint16_t* z[2] = {nullptr, nullptr}; // word-major assignments
+    uint16_t* z_doc = nullptr;           // streamed: the same in document order (in doc_map's place)
     int cur = 0;
     uint2* row_rec = nullptr;
     unsigned char* slots = nullptr;
@@ -442,6 +444,8 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
     c->tok_id = (int32_t*)(base + h.L.tok_id);
     c->doc_map = (int32_t*)(base + h.L.doc_map);
+    c->block_doc = (int32_t*)(base + h.L.block_doc);
+    c->z_doc = (uint16_t*)(base + h.L.doc_map);   // a streamed chunk needs no map, see derive_chunk_arrays
     c->doc_ptr = (int32_t*)(base + h.L.doc_ptr);
     c->doc_order = (mlda::DocRec*)(base + h.L.doc_order);
     c->row_rec = (uint2*)(base + h.L.row_rec);
@@ -462,9 +466,18 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
 // After the static part of a chunk has arrived: the index arrays that follow from it
 // (document->token map, slot of every token's theta row), and what a lane of the sampler
 // reads when it has no entries of its own: four padding entries (count 0, topic K) at the
-// start of the slot buffer.
+// start of the slot buffer.  A streamed chunk arrives with its assignments in document order
+// and hands them back so: its theta rebuilds read them directly and it needs no map (building
+// one costs as much as a theta rebuild); the tokens' slots are then found by bisection.
 void derive_chunk_arrays(mlda_ctx* c) {
-    if (c->T > 0) {
+    if (c->T > 0 && c->streamed) {
+        const int64_t n_blocks = c->T / 64 + 1;
+        hipLaunchKernelGGL(mlda::derive_block_doc_kernel, dim3(blocks_for(n_blocks, 256)), dim3(256), 0,
+                           c->stream, c->doc_ptr, (int32_t)c->D, n_blocks, c->block_doc);
+        hipLaunchKernelGGL(mlda::derive_tok_slot_by_search_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                           c->stream, c->tok_id, c->T, c->at->tok_begin, c->doc_ptr, (int32_t)c->D,
+                           c->block_doc, c->row_rec, c->tok_slot);
+    } else if (c->T > 0) {
         hipLaunchKernelGGL(mlda::derive_doc_map_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
                            c->tok_id, c->T, c->at->tok_begin, c->doc_map);
         const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * 32);
@@ -476,9 +489,9 @@ void derive_chunk_arrays(mlda_ctx* c) {
 }
 
 // Streamed: bring chunk m into the slot of this visit.  The static part (and with_z: the
-// chunk's assignments, caller's order, into z[1]) is copied on the copy stream, so that it
+// chunk's assignments, caller's order, into z_doc) is copied on the copy stream, so that it
 // overlaps the kernels of the chunk before; the context's stream then waits for it and, with_z,
-// turns the assignments into word-major order in z[0].
+// also puts the assignments in word-major order into z[0].
 int attach(mlda_ctx* c, int32_t m, bool with_z) {
     const HostChunk& h = c->chunks[(size_t)m];
     const int s = (int)(c->visits % 2);
@@ -491,7 +504,7 @@ int attach(mlda_ctx* c, int32_t m, bool with_z) {
                                c->copy_stream));
     if (with_z && h.T > 0) {
         HIP_TRY(hipStreamWaitEvent(c->copy_stream, c->z_stored[(size_t)m], 0));
-        HIP_TRY(hipMemcpyAsync(c->z[1], c->z_host + h.tok_begin, (size_t)h.T * 2, hipMemcpyHostToDevice,
+        HIP_TRY(hipMemcpyAsync(c->z_doc, c->z_host + h.tok_begin, (size_t)h.T * 2, hipMemcpyHostToDevice,
                                c->copy_stream));
     }
     HIP_TRY(hipEventRecord(c->slot_ready[s], c->copy_stream));
@@ -499,24 +512,28 @@ int attach(mlda_ctx* c, int32_t m, bool with_z) {
     derive_chunk_arrays(c);
     if (with_z && h.T > 0)
         hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
-                           c->z[1], c->tok_id, c->z[0], h.T, h.tok_begin);
+                           c->z_doc, c->tok_id, c->z[0], h.T, h.tok_begin);
     return launch_check("attaching a chunk");
 }
 
-// Streamed: the attached chunk's assignments z (word-major) go back to the host, and the
+// Streamed: new word-major assignments of the attached chunk, put in document order too.
+int to_document_order(mlda_ctx* c, const uint16_t* z_word) {
+    if (c->T > 0)
+        hipLaunchKernelGGL(mlda::to_doc_major_scatter_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
+                           c->stream, z_word, c->tok_id, c->z_doc, c->T, c->at->tok_begin);
+    return launch_check("to_doc_major_scatter_kernel");
+}
+
+// Streamed: the attached chunk's assignments (z_doc) go back to the host if `store`, and the
 // chunk's slot is free again once everything queued so far is done.
-int store_z_and_release(mlda_ctx* c, int32_t m, const uint16_t* z_word, bool store) {
+int store_z_and_release(mlda_ctx* c, int32_t m, bool store) {
     const HostChunk& h = c->chunks[(size_t)m];
     const int s = (int)((c->visits - 1) % 2);
     if (store && h.T > 0) {
-        uint16_t* tmp = (z_word == c->z[0]) ? c->z[1] : c->z[0];
-        hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
-                           z_word, c->doc_map, tmp, h.T);
-        RC_TRY(launch_check("to_doc_major_kernel"));
         // the download runs on its own stream, beside the next chunk's kernels and upload
         HIP_TRY(hipEventRecord(c->z_ready, c->stream));
         HIP_TRY(hipStreamWaitEvent(c->down_stream, c->z_ready, 0));
-        HIP_TRY(hipMemcpyAsync(c->z_host + h.tok_begin, tmp, (size_t)h.T * 2, hipMemcpyDeviceToHost,
+        HIP_TRY(hipMemcpyAsync(c->z_host + h.tok_begin, c->z_doc, (size_t)h.T * 2, hipMemcpyDeviceToHost,
                                c->down_stream));
         HIP_TRY(hipEventRecord(c->z_stored[(size_t)m], c->down_stream));
         HIP_TRY(hipEventRecord(c->slot_free[s], c->down_stream));
@@ -580,22 +597,24 @@ int finish_model(mlda_ctx* c, int which) {
     return launch_check("topic totals");
 }
 
-// theta rows of the attached chunk from its assignments z (word-major); leaves the rows' part
-// of the log-likelihood as one partial per workgroup in ll_partial[2 kLoglikBlocks ..].
+// theta rows of the attached chunk from its assignments: z word-major, reached through the
+// document->token map; streamed: z = z_doc, read directly.  Leaves the rows' part of the
+// log-likelihood as one partial per workgroup in ll_partial[2 kLoglikBlocks ..].
 int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
     using namespace mlda;
+    const int32_t* doc_map = c->streamed ? nullptr : c->doc_map;
     if (c->D > 0) {
         const size_t theta_lds = theta_lds_bytes(c->K, c->packed);
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
         if (c->packed)
             hipLaunchKernelGGL(theta_rows_kernel<true>, dim3((unsigned)c->theta_grid), dim3(kWave),
-                               theta_lds, c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
+                               theta_lds, c->stream, c->doc_order, doc_map, z, c->row_rec, c->slots,
                                c->D, c->K, c->alpha, c->lg_table, entries,
                                c->ll_partial + 2 * kLoglikBlocks);
         else
             hipLaunchKernelGGL(theta_rows_kernel<false>, dim3((unsigned)c->theta_grid), dim3(kWave),
-                               theta_lds, c->stream, c->doc_order, c->doc_map, z, c->row_rec, c->slots,
+                               theta_lds, c->stream, c->doc_order, doc_map, z, c->row_rec, c->slots,
                                c->D, c->K, c->alpha, c->lg_table, entries,
                                c->ll_partial + 2 * kLoglikBlocks);
     }
@@ -848,7 +867,8 @@ int rebuild_model_streamed(mlda_ctx* c, bool init) {
             hipLaunchKernelGGL(mlda::init_topics_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
                                c->tok_id, c->z[0], c->T, c->K, c->seed);
         RC_TRY(rebuild_phi(c, c->z[0], c->model_cur));
-        RC_TRY(store_z_and_release(c, m, c->z[0], init));
+        if (init) RC_TRY(to_document_order(c, c->z[0]));
+        RC_TRY(store_z_and_release(c, m, init));
     }
     return finish_model(c, c->model_cur);
 }
@@ -861,11 +881,11 @@ int for_each_chunk_rows(mlda_ctx* c, F&& visit) {
     for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
         if (c->chunks[(size_t)m].D == 0) continue;
         RC_TRY(attach(c, m, true));
-        RC_TRY(rebuild_theta(c, c->z[0]));
+        RC_TRY(rebuild_theta(c, c->z_doc));
         RC_TRY(add_theta_loglik(c, first));
         first = false;
         RC_TRY(visit(c->chunks[(size_t)m]));
-        RC_TRY(store_z_and_release(c, m, c->z[0], false));
+        RC_TRY(store_z_and_release(c, m, false));
     }
     if (first) {            // no documents at all: the sum is empty
         hipLaunchKernelGGL(mlda::loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, 0,
@@ -1081,15 +1101,16 @@ static int step_streamed(mlda_ctx* c, bool loglik) {
     for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
         if (c->chunks[(size_t)m].D == 0) continue;
         RC_TRY(attach(c, m, true));
-        RC_TRY(rebuild_theta(c, c->z[0]));             // theta is not kept between visits
+        RC_TRY(rebuild_theta(c, c->z_doc));            // theta is not kept between visits
         RC_TRY(launch_sampler(c, c->z[0], c->z[1]));
         RC_TRY(rebuild_phi(c, c->z[1], next));
+        RC_TRY(to_document_order(c, c->z[1]));
         if (loglik) {
-            RC_TRY(rebuild_theta(c, c->z[1]));
+            RC_TRY(rebuild_theta(c, c->z_doc));
             RC_TRY(add_theta_loglik(c, first));
             first = false;
         }
-        RC_TRY(store_z_and_release(c, m, c->z[1], true));
+        RC_TRY(store_z_and_release(c, m, true));
     }
     RC_TRY(finish_model(c, next));
     c->model_cur = next;
