@@ -318,6 +318,121 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     block_partial_store(ll, ll_partial);
 }
 
+// The same for rows with 4-byte entries and K <= 1024, two documents per wave: the mark bits
+// of a document then fit one word per lane of a half-wave (32 lanes x 32 topics), so lanes
+// 0..31 rebuild one document and lanes 32..63 the next one with the same instructions, which
+// halves the instructions per document.  Documents 2 p and 2 p + 1 (neighbours in the working
+// order, so of similar length) make pair p; the topics of the first 128 tokens of each document
+// of the next pair are on their way while the current pair is counted.
+constexpr int kPairMaxK = 1024;
+
+__global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* docs,
+                                                                const int32_t* doc_map,
+                                                                const uint16_t* z, uint2* row_rec,
+                                                                unsigned char* slots, int64_t D,
+                                                                int32_t K, double alpha,
+                                                                const double* lg_table,
+                                                                unsigned long long* row_entries,
+                                                                double* ll_partial) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = (int)threadIdx.x, half = lane >> 5, hl = lane & 31;
+    const int n_counters = (K + 1) / 2, n_marks = (K + 31) / 32;
+    const size_t one = theta_hist_bytes(K, true);
+    // per half: paired 16-bit counters, then one mark bit per topic
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds + (size_t)half * one);
+    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (size_t)half * one +
+                                                  (((size_t)n_counters * 4 + 15) & ~(size_t)15));
+    double* table = reinterpret_cast<double*>(lds + 2 * one);
+    const double lg_alpha = lg_table[kLgTable];
+    for (int k = hl; k < n_counters; k += 32) hist[k] = 0u;
+    for (int k = hl; k < n_marks; k += 32) marks[k] = 0u;
+    for (int c = lane; c < kThetaLgTable; c += kWave) table[c] = lg_table[c];
+    __syncthreads();
+    unsigned long long visited = 0;      // sum of N_d * nnz_d over this half's documents
+    double ll = 0.0;
+    auto add_ll = [&](int c) {
+        if (c > 0 && c < kThetaLgTable) ll += table[c];
+        if (__ballot(c >= kThetaLgTable) != 0) {
+            if (c >= kThetaLgTable)
+                ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
+        }
+    };
+    auto count_topic = [&](int k) {
+        atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
+        atomicOr(&marks[k >> 5], 1u << (k & 31));
+    };
+    auto topic_at = [&](const DocRec& r, int j) {       // topic of the document's token j, -1 past its end
+        const int p = doc_token_position(doc_map, r, j);
+        return p >= 0 ? (int)z[p] : -1;
+    };
+    const int64_t n_pairs = (D + 1) / 2, step = gridDim.x;
+    const DocRec none = {0, 0, 0u, 0};
+    auto record = [&](int64_t p) { return (p < n_pairs && 2 * p + half < D) ? docs[2 * p + half] : none; };
+    // each XCD takes a contiguous run of pairs (see theta_rows_kernel)
+    const int per_xcd = (int)gridDim.x / kXcds;
+    int64_t i = (int)blockIdx.x < per_xcd * kXcds
+                    ? (int64_t)((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds
+                    : (int64_t)blockIdx.x;
+    DocRec cur = record(i), nxt = record(i + step);
+    int k0 = topic_at(cur, hl), k1 = topic_at(cur, hl + 32), k2 = topic_at(cur, hl + 64),
+        k3 = topic_at(cur, hl + 96);
+    for (; i < n_pairs; i += step) {
+        const int n0 = topic_at(nxt, hl), n1 = topic_at(nxt, hl + 32), n2 = topic_at(nxt, hl + 64),
+                  n3 = topic_at(nxt, hl + 96);
+        const DocRec after = record(i + 2 * step);
+        if (k0 >= 0) count_topic(k0);
+        if (k1 >= 0) count_topic(k1);
+        if (k2 >= 0) count_topic(k2);
+        if (k3 >= 0) count_topic(k3);
+        for (int j = 128 + hl; j < cur.n; j += 32) count_topic(topic_at(cur, j));
+        __syncthreads();
+        unsigned char* head = slots + (size_t)cur.slot * 16u;
+        uint32_t* ent = reinterpret_cast<uint32_t*>(head + kRowHeader);
+        // lane hl of a half owns mark word hl: 32 topics = 16 counter pairs
+        const uint32_t w = hl < n_marks ? marks[hl] : 0u;
+        const int mine = __popc(w);
+        // prefix over the 32 lanes of each half: the wave-wide scan without its last step
+        int upto = mine;
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x111, 0xf, 0xf, false);
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x112, 0xf, 0xf, false);
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x114, 0xf, 0xf, false);
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x118, 0xf, 0xf, false);
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x142, 0xa, 0xf, false);
+        const int nnz_a = read_lane(upto, 31), nnz_b = read_lane(upto, 63);
+        const int nnz = half ? nnz_b : nnz_a;
+        int at = upto - mine;
+        if (w != 0u) marks[hl] = 0u;
+        uint32_t pairs = (w | (w >> 1)) & 0x55555555u;
+        while (__ballot(pairs != 0u) != 0) {
+            int lo = 0, hi = 0;
+            if (pairs != 0u) {
+                const int k = hl * 32 + __ffs((int)pairs) - 1;    // even topic of the pair
+                pairs &= pairs - 1u;
+                const uint32_t both = hist[k >> 1];
+                hist[k >> 1] = 0u;
+                lo = (int)(both & 0xffffu);
+                hi = (int)(both >> 16);
+                if (lo != 0) ent[at++] = ((uint32_t)lo << 18) | ((uint32_t)k << 2);
+                if (hi != 0) ent[at++] = ((uint32_t)hi << 18) | ((uint32_t)(k + 1) << 2);
+            }
+            add_ll(lo);
+            add_ll(hi);
+        }
+        const bool real = 2 * i + half < D;              // the last pair may lack its second document
+        const int nnz_pad = (nnz + 3) & ~3;
+        if (real && hl < nnz_pad - nnz) ent[nnz + hl] = (uint32_t)K << 2;
+        if (real && hl == 0) {
+            *reinterpret_cast<uint32_t*>(head) = (uint32_t)nnz;
+            row_rec[cur.doc].y = (uint32_t)nnz;
+            visited += (unsigned long long)cur.n * (unsigned long long)nnz;
+        }
+        __syncthreads();
+        cur = nxt; nxt = after; k0 = n0; k1 = n1; k2 = n2; k3 = n3;
+    }
+    if (hl == 0 && visited != 0) atomicAdd(row_entries, visited);
+    block_partial_store(ll, ll_partial);
+}
+
 // The two per-token index arrays that follow from tok_id and the document records are built
 // on the device rather than sent over PCIe.  doc_map (Section 6.2's document->token map) is the
 // inverse of tok_id; tokens are numbered from `first` inside a chunk.

@@ -607,7 +607,13 @@ int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
         const size_t theta_lds = theta_lds_bytes(c->K, c->packed);
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
-        if (c->packed)
+        // two documents per wave where a half-wave suits them: few topics, short documents
+        if (c->packed && c->K <= kPairMaxK && c->T <= 160 * c->D)
+            hipLaunchKernelGGL(theta_rows_pair_kernel, dim3((unsigned)c->theta_grid), dim3(kWave),
+                               2 * theta_hist_bytes(c->K, true) + (size_t)kThetaLgTable * 8, c->stream,
+                               c->doc_order, doc_map, z, c->row_rec, c->slots, c->D, c->K, c->alpha,
+                               c->lg_table, entries, c->ll_partial + 2 * kLoglikBlocks);
+        else if (c->packed)
             hipLaunchKernelGGL(theta_rows_kernel<true>, dim3((unsigned)c->theta_grid), dim3(kWave),
                                theta_lds, c->stream, c->doc_order, doc_map, z, c->row_rec, c->slots,
                                c->D, c->K, c->alpha, c->lg_table, entries,
