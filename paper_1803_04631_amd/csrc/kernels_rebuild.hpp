@@ -33,7 +33,14 @@ __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const u
     const int tid = (int)threadIdx.x;
     for (int k = tid; k < K; k += 256) hist[k] = 0;
     __syncthreads();
-    for (int i = tid; i < tl.count; i += 256) atomicAdd(&hist[z[tl.begin + i]], 1);
+    // four independent loads in flight per thread: the loop is bound by their latency
+    const uint16_t* zt = z + tl.begin;
+    int i = tid;
+    for (; i + 768 < tl.count; i += 1024) {
+        const int k0 = zt[i], k1 = zt[i + 256], k2 = zt[i + 512], k3 = zt[i + 768];
+        atomicAdd(&hist[k0], 1); atomicAdd(&hist[k1], 1); atomicAdd(&hist[k2], 1); atomicAdd(&hist[k3], 1);
+    }
+    for (; i < tl.count; i += 256) atomicAdd(&hist[zt[i]], 1);
     __syncthreads();
     int32_t* row = n_wk + (size_t)tl.word * (size_t)K;
     if (tl.whole) {
