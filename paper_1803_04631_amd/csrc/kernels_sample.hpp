@@ -10,10 +10,10 @@
 //   - each wave takes 64 tokens at a time.  What is per token and needs no cooperation is
 //     done one token per LANE: the Philox uniform, the token's own-count correction of
 //     p*(o), and the search in the dense bucket p2 (binary search over the group prefixes,
-//     then the group's four topics);
+//     then the group's topics);
 //   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
 //     by a GROUP of 4, 8, 16, 32 or 64 lanes per token, chosen per pass from the row lengths
-//     so that a lane owns at most eight entries (16, 8, 4, 2 or 1 tokens per pass: the fixed
+//     so that a lane owns at most twelve entries (16, 8, 4, 2 or 1 tokens per pass: the fixed
 //     cost of a pass is shared by as many tokens as their rows allow).  Groups narrower than
 //     a DPP row of 16 lanes are interleaved inside the row (4 or 2 tokens side by side), so
 //     that plain row shifts scan every group at once.  Every lane owns a contiguous run of
