@@ -216,7 +216,9 @@ struct PackedRows {
     static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int,
                                                int e, bool on, int) {
         static_assert(kRowHeader == 16, "a row's entries start one 16-byte unit into its slot");
-        const uint32_t unit = on ? off + 1u + ((uint32_t)e >> 2) : 0u;
+        uint32_t unit = on ? off + 1u + ((uint32_t)e >> 2) : 0u;
+        // the choice is made on the 32-bit unit number, before it becomes a 64-bit address
+        asm volatile("" : "+v"(unit));
         Raw q;
         q.e = *reinterpret_cast<const uint4*>(slots + (size_t)unit * 16u);
         return q;
@@ -434,8 +436,8 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     __syncthreads();
 
     // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
-    // place inside its group, its first entry
-    int geo_shape = -1, geo_rel = 0, geo_sl = 0, geo_e0 = 0;
+    // place inside its group, its first quad of entries
+    int geo_shape = -1, geo_rel = 0, geo_sl = 0, geo_q0 = 0;
     const int n_batches = (tl.count + kWave - 1) / kWave;
     for (int b = wave; b < n_batches; b += kWaves) {
         // ---- one token per lane: token, uniform, own-count correction
@@ -507,16 +509,17 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
                 geo_shape = shape;
                 geo_rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
                 geo_sl = (lane & ((1 << hs) - 1)) >> g;
-                geo_e0 = geo_sl * (4 * nq);
+                geo_q0 = geo_sl * nq;        // the lane's first quad
             }
             sl = geo_sl;
             rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             const int nnz = (int)where.y;
-            const int e0 = geo_e0;
+            // quads the lane loads: those of the shape that the row still has from q0 on
+            const int n_mine = min(((nnz + 3) >> 2) - geo_q0, nq);
 #pragma unroll
             for (int c = 0; c < kKeptQuads; ++c)
-                raw[c] = Layout::load(a.slots, where.x, nnz, e0 + 4 * c, c < nq && e0 + 4 * c < nnz, K);
+                raw[c] = Layout::load(a.slots, where.x, nnz, 4 * (geo_q0 + c), c < n_mine, K);
         };
         int t_next = 0, shape_next = shape_at(0), sl_next;
         TokenRec* rec_next;
