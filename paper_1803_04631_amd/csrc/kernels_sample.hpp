@@ -485,7 +485,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         const uint64_t over512 = __ballot(mine.nnz > 512), over768 = __ballot(mine.nnz > 768);
         auto any = [](uint64_t mask, int t0, uint32_t window) {      // 1 if a token of the window is set
             const uint32_t w = (uint32_t)(mask >> t0) & window;
-            return (int)((w | (0u - w)) >> 31);
+            return min(1, (int)__builtin_popcount(w));      // stays scalar arithmetic
         };
         auto shape_at = [&](int t0) {
             if (!any(over32, t0, 0xffffu)) return any(over16, t0, 0xffffu);
