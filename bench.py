@@ -30,6 +30,14 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# The paper's own single-GPU rates (its Table 4, mean of the first 100 iterations) on the
+# collections that C3 and C4 are shaped like: context, never a baseline for `vs_baseline`.
+PAPER_CONTEXT = {
+    "C3": "paper, NYTimes: 173.6 M tokens/s on TITAN X (Maxwell), 208.0 M on Titan Xp, 633.0 M on V100",
+    "C4": "paper, PubMed: 155.6 M tokens/s on TITAN X (Maxwell), 213.0 M on Titan Xp, 686.2 M on V100",
+}
+
+
 def paper_unshared_accounting(k_d, k, int_bytes=4, float_bytes=4):
     """The paper's Table 1: flops and bytes per token of the four sampler steps when nothing
     is shared between samplers (32-bit integers and floats).  Returns {step: (flops, bytes)}."""
@@ -200,6 +208,8 @@ def main():
             "loglik_per_token": ll / T,
             "theta_nnz_per_doc": nnz / cfg.D,
             "sampler_bytes_per_token": float(algo_bytes.mean()) / T,
+            # context only (other hardware, the real collections, K not stated): the paper's Table 4
+            "paper_context": PAPER_CONTEXT.get(cfg.name),
         },
         "roofline": {
             "kernel": "sample_kernel",
