@@ -536,7 +536,19 @@ __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_
     };
     const int64_t n_quads = n_cells / 4, stride = (int64_t)gridDim.x * blockDim.x;
     const int4* quads = reinterpret_cast<const int4*>(n_wk);
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_quads; i += stride) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n_quads; i += 4 * stride) {        // four loads in flight per thread
+        const int4 v0 = quads[i], v1 = quads[i + stride], v2 = quads[i + 2 * stride],
+                   v3 = quads[i + 3 * stride];
+        if (__ballot((v0.x | v0.y | v0.z | v0.w | v1.x | v1.y | v1.z | v1.w | v2.x | v2.y | v2.z | v2.w |
+                      v3.x | v3.y | v3.z | v3.w) != 0) == 0)
+            continue;
+        add_cell(v0.x); add_cell(v0.y); add_cell(v0.z); add_cell(v0.w);
+        add_cell(v1.x); add_cell(v1.y); add_cell(v1.z); add_cell(v1.w);
+        add_cell(v2.x); add_cell(v2.y); add_cell(v2.z); add_cell(v2.w);
+        add_cell(v3.x); add_cell(v3.y); add_cell(v3.z); add_cell(v3.w);
+    }
+    for (; i < n_quads; i += stride) {
         const int4 v = quads[i];
         if (__ballot((v.x | v.y | v.z | v.w) != 0) == 0) continue;
         add_cell(v.x); add_cell(v.y); add_cell(v.z); add_cell(v.w);
