@@ -35,7 +35,7 @@
  *     torch.cuda.current_stream().cuda_stream); the library allocates no device
  *     memory, keeps the workspace until mlda_destroy, and launches all kernels on
  *     that stream (a context made by mlda_create_streamed also owns pinned host
- *     memory and a copy stream).  Getters synchronise the stream.
+ *     memory and two copy streams).  Getters synchronise the stream.
  *   - A context is not thread-safe.  Token order at the boundary is always the
  *     caller's document-major order; the word-major order used on the device is
  *     internal.
@@ -68,7 +68,8 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
 
 /*
  * Build a context (Section 2.1: the corpus; Section 6.1.2: tokens are put in
- * word-first order; Section 6.2: a document->token map is built on the CPU).
+ * word-first order, on the host; Section 6.2: a document->token map, which the paper
+ * builds on the CPU, is derived on the device).
  *   doc_ptr   host, D+1 entries, doc_ptr[0] = 0, non-decreasing; document d owns
  *             tokens doc_ptr[d] .. doc_ptr[d+1]-1.  T = doc_ptr[D] < 2^31.
  *   word_ids  host, T entries, each in [0,V).
@@ -87,11 +88,11 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
  * WorkSchedule2: with more than one chunk per GPU the chunks are transferred every
  * iteration, phi stays on the device).  For corpora whose tokens and theta rows do not fit
  * the device beside phi.  The preprocessed chunks and all assignments are kept in pinned
- * host memory that the library allocates; per iteration every chunk is uploaded (on a second
- * stream of default priority that the library creates, overlapping the kernels of the chunk
+ * host memory that the library allocates; per iteration every chunk is uploaded (on a stream
+ * of default priority that the library creates, overlapping the kernels of the chunk
  * before), its theta rows are rebuilt from its assignments, it is sampled against the phi of
  * the iteration's start, its counts are added to the next phi, and its new assignments go
- * back to the host.  Results are identical, bit for bit, to those of mlda_create: the counts
+ * back to the host (on a second such stream).  Results are identical, bit for bit, to those of mlda_create: the counts
  * of an iteration are frozen and the uniforms are keyed by the caller's token index.
  * The workspace (mlda_workspace_bytes_streamed: two copies of phi and two chunk buffers) and
  * the other arguments are as for mlda_create; doc_ptr is read by the sizing call too.
@@ -163,7 +164,7 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
  */
 int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);
 
-/* Releases the context (host memory, events, its copy stream if any); the workspace stays
+/* Releases the context (host memory, events, its copy streams if any); the workspace stays
  * the caller's. */
 void mlda_destroy(mlda_ctx* ctx);
 
