@@ -2,8 +2,8 @@
 //
 // Paper sections behind the host steps: Section 6.1.2 (tokens are sorted word-first and
 // the tokens of heavy words are split over several workgroups), Section 6.2 (a
-// document->token map built on the CPU lets the theta update find a document's tokens in
-// the word-sorted arrays), Section 4 and Algorithm 1 (the corpus is partitioned by document
+// document->token map lets the theta update find a document's tokens in the word-sorted
+// arrays; the paper builds it on the CPU, here it is derived on the device), Section 4 and Algorithm 1 (the corpus is partitioned by document
 // into chunks; WorkSchedule1: one chunk, transferred once, iterated on the device;
 // WorkSchedule2: several chunks per GPU, transferred every iteration while phi stays).
 //
