@@ -292,7 +292,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
     mlda::Tile* segs = (mlda::Tile*)(h.arena + h.L.segs);
     int32_t* split_words = (int32_t*)(h.arena + h.L.split);
 
-    // (the slot of every tile's first document orders the tiles below)
+    // (the slot of every tile's middle document orders the tiles below)
     std::vector<uint32_t> tile_key;
     std::vector<int32_t> tile_base;
     try {
@@ -312,7 +312,10 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
                 const int32_t w = word_ids[t];
                 const int32_t in_word = start[w]++;
                 tok_id[word_ptr[w] + in_word] = (int32_t)(tok_begin + t);   // the caller's token index keys the uniforms
-                if (in_word % tile == 0) tile_key[(size_t)(tile_base[w] + in_word / tile)] = slot_of[(size_t)d];
+                // the tile's middle token names the document whose slot is the tile's sort key
+                const int32_t in_tile = in_word % tile;
+                const int32_t tile_len = std::min(tile, word_ptr[w + 1] - word_ptr[w] - (in_word - in_tile));
+                if (in_tile == tile_len / 2) tile_key[(size_t)(tile_base[w] + in_word / tile)] = slot_of[(size_t)d];
             }
         }
     });
@@ -338,7 +341,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
                                     (!accumulate && n <= kPhiSegment) ? 1 : 0};
     }
     try {
-        // Sampling tiles run in the order of their first document (longest documents first;
+        // Sampling tiles run in the order of their middle document (longest documents first;
         // slot offsets rise in that order), not word by word: tiles of different words that
         // are in flight together then walk the theta rows of the same documents, which are
         // fetched from HBM once instead of once per heavy word.  (The paper issues the tiles
