@@ -60,6 +60,7 @@ constexpr int kRowHeader = 16;  // bytes before a theta row's entries
 // waves, K <= 2048), 16 for the large-K workgroups of twelve waves.
 __host__ __device__ constexpr int dense_group(int waves) { return waves == 4 ? 4 : 16; }
 constexpr int kKeptQuads = 3;   // quads (of four entries) a lane keeps in registers at most
+constexpr int kMinBatch = 8;    // tokens a wave takes at a time at least
 
 // Once a token's pass has read its record, the record takes the result back to the per-lane
 // phase: the new topic (or -1 for "dense bucket") in `off`, the dense draw position in `u`.
@@ -438,11 +439,16 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
     // place inside its group, its first quad of entries
     int geo_shape = -1, geo_rel = 0, geo_sl = 0, geo_q0 = 0;
-    const int n_batches = (tl.count + kWave - 1) / kWave;
+    // A wave takes up to 64 tokens at a time.  A tile too small to give every wave such a batch
+    // is dealt out in smaller batches, so that all waves work on it side by side: the passes
+    // of one batch follow each other, each waiting for its rows.
+    const int batch = kWaves == 4 ? kWave
+                    : min(kWave, max(kMinBatch, ((tl.count + kWaves - 1) / kWaves + 3) & ~3));
+    const int n_batches = (tl.count + batch - 1) / batch;
     for (int b = wave; b < n_batches; b += kWaves) {
         // ---- one token per lane: token, uniform, own-count correction
-        const int idx = b * kWave + lane;
-        const bool valid = idx < tl.count;
+        const int idx = b * batch + lane;
+        const bool valid = lane < batch && idx < tl.count;
         const int pos = tl.begin + idx;
         TokenRec mine;
         mine.off = 0; mine.nnz = 0; mine.o = 0; mine.w_o = 0.f; mine.u = 0.0; mine.Qp = 0.0;
@@ -470,13 +476,13 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // ---- one token per group of 4 .. 64 lanes.  A pass takes the next 16, 8, 4, 2 or 1
         // tokens, as many as lets every lane own at most kKeptQuads quads; the rows of the
         // following pass are requested from memory before this one is worked on.
-        const int n_here = min(kWave, tl.count - b * kWave);
         // Shapes of a pass (lanes per token, quads per lane -> entries per row at most):
         //   0 (4,1) 16   1 (4,2) 32   2 (8,2) 64   3 (8,3) 96   4 (16,2) 128   5 (16,3) 192
         //   6 (32,2) 256   7 (32,3) 384   8 (64,2) 512   9 (64,3) 768
         //   10 = one longer row, walked twice by the wave
         // Which tokens of the batch have rows beyond each of these lengths (lanes past the
         // batch's end hold nnz = 0): the shape of every pass follows from these masks.
+        const int n_here = min(batch, tl.count - b * batch);
         static_assert(kKeptQuads == 3, "the pass shapes assume three kept quads per lane");
         const uint64_t over16 = __ballot(mine.nnz > 16), over32 = __ballot(mine.nnz > 32);
         const uint64_t over64 = __ballot(mine.nnz > 64), over96 = __ballot(mine.nnz > 96);
@@ -560,7 +566,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // ---- one token per lane again: dense bucket, store
         // (the token's topic and corrected weight are read back from its record rather than
         // kept in registers across the passes)
-        if (b * kWave + lane < tl.count) {
+        if (lane < batch && b * batch + lane < tl.count) {
             const TokenRec* rec = &my_rec[lane];
             int z_new = (int)rec->off;
             if (z_new < 0) {
@@ -569,7 +575,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
                 z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, o, w_o,
                                                     (double)w_o - (double)pstar[o]);
             }
-            a.z_next[tl.begin + b * kWave + lane] = (uint16_t)z_new;
+            a.z_next[tl.begin + b * batch + lane] = (uint16_t)z_new;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
