@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per sampling launch from rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by a
 # copy kernel of known size); filled in from the summaries under profiles/ per workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/sample_kernel_C4.md: FETCH_SIZE 1.1924e8 KiB x 2.000 + WRITE_SIZE 2.4774e6 KiB x 1.000
-    ("C4", "init"): (1.1924e8 * 2.000 + 2.4774e6 * 1.000) * 1024.0,
+    # profiles/sample_kernel_C4.md: FETCH_SIZE 1.17496e8 KiB x 2.000 + WRITE_SIZE 2.4738e6 KiB x 1.000
+    ("C4", "init"): (1.17496e8 * 2.000 + 2.4738e6 * 1.000) * 1024.0,
 }
 
 

@@ -126,8 +126,9 @@ int mlda_iteration(const mlda_ctx* ctx, int32_t* iter);
 /* Current assignments, document-major.  z: host, T entries, out. */
 int mlda_get_assignments(mlda_ctx* ctx, uint16_t* z);
 
-/* phi as a word-major matrix: n_wk[v*K + k] = tokens of word v with topic k.
- * n_wk: host, V*K entries, out. */
+/* phi as a word-major matrix: n_wk[v*K + k] = tokens of word v with topic k, exact (on the
+ * device 16-bit cells, int32 for words with 2^16 tokens or more; widened here on the host,
+ * which takes V*K*2 bytes of temporary host memory).  n_wk: host, V*K entries, out. */
 int mlda_get_word_topic(mlda_ctx* ctx, int32_t* n_wk);
 
 /* n_k[k] = sum_v phi_kv, the denominator term of Eq. 1.  n_k: host, K entries, out. */
@@ -159,7 +160,8 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
  * (Section 3.1's accounting, with p* shared per word tile): per token 16 bytes (slot of
  * its theta row, token id, old and new topic, row length) plus 4 bytes per entry of its theta row
  * (6 if some document has 2^14 or more tokens: counts then need their own 32-bit words),
- * plus 4 K bytes of phi per tile.  bytes: host, capacity_iters doubles, out; rows as in
+ * plus the word's row of phi per tile: 2 K bytes (Section 6.1.3: short integers), 4 K for a word
+ * with 2^16 tokens or more, whose counts the library keeps as int32.  bytes: host, capacity_iters doubles, out; rows as in
  * mlda_get_timing.
  */
 int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);

@@ -16,17 +16,21 @@ __global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
 
 // Rows of words whose tokens span several segments are accumulated with atomics and must
 // start at zero.  grid = (#split words, ceil(K / blockDim)).
-__global__ void zero_rows_kernel(const int32_t* words, int32_t* n_wk, int32_t K) {
+__global__ void zero_rows_kernel(const int32_t* words, PhiView phi, int32_t K) {
     const int k = (int)(blockIdx.y * blockDim.x + threadIdx.x);
-    if (k < K) n_wk[(size_t)words[blockIdx.x] * (size_t)K + k] = 0;
+    if (k >= K) return;
+    const int v = words[blockIdx.x], wide_row = phi.wide_row[v];
+    if (wide_row >= 0) phi.wide[(size_t)wide_row * (size_t)K + k] = 0;
+    else phi.narrow[(size_t)v * (size_t)K + k] = 0;
 }
 
 // Update phi (Section 6.2: word by word, atomics with good locality): a workgroup
 // histograms one segment (up to 16384 consecutive tokens of one word) in LDS, then stores
 // the word's row outright if the segment is the whole word, else adds its non-zero bins
-// to the row.
+// to the row.  A 16-bit cell is added to through the aligned dword that holds it: the word has
+// fewer than 2^16 tokens, so no sum carries into the neighbouring cell.
 __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const uint16_t* z,
-                                                       int32_t* n_wk, int32_t K) {
+                                                       PhiView phi, int32_t K) {
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* hist = reinterpret_cast<int32_t*>(lds);
     const Tile tl = segs[blockIdx.x];
@@ -42,13 +46,28 @@ __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const u
     }
     for (; i < tl.count; i += 256) atomicAdd(&hist[zt[i]], 1);
     __syncthreads();
-    int32_t* row = n_wk + (size_t)tl.word * (size_t)K;
-    if (tl.whole) {
-        for (int k = tid; k < K; k += 256) row[k] = hist[k];
+    const int wide_row = phi.wide_row[tl.word];
+    if (wide_row >= 0) {
+        int32_t* row = phi.wide + (size_t)wide_row * (size_t)K;
+        if (tl.whole) {
+            for (int k = tid; k < K; k += 256) row[k] = hist[k];
+        } else {
+            for (int k = tid; k < K; k += 256) {
+                const int c = hist[k];
+                if (c != 0) atomicAdd(&row[k], c);
+            }
+        }
     } else {
-        for (int k = tid; k < K; k += 256) {
-            const int c = hist[k];
-            if (c != 0) atomicAdd(&row[k], c);
+        const size_t cell0 = (size_t)tl.word * (size_t)K;
+        if (tl.whole) {
+            for (int k = tid; k < K; k += 256) phi.narrow[cell0 + k] = (uint16_t)hist[k];
+        } else {
+            uint32_t* dwords = reinterpret_cast<uint32_t*>(phi.narrow);
+            for (int k = tid; k < K; k += 256) {
+                const uint32_t c = (uint32_t)hist[k];
+                const size_t cell = cell0 + k;
+                if (c != 0) atomicAdd(&dwords[cell >> 1], c << ((cell & 1) * 16));
+            }
         }
     }
 }
@@ -74,16 +93,17 @@ __global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, in
 
 // The same totals as column sums of n_wk (cheaper than a pass over z when V K is small next to
 // T): thread x of a workgroup owns topic blockIdx.x * 256 + x, workgroup row blockIdx.y a
-// slice of the words; reads are coalesced along a word's row.  n_k must be zero on entry.
-__global__ __launch_bounds__(256) void topic_totals_from_rows_kernel(const int32_t* n_wk, int32_t V,
+// slice of the words, and the same slice of the wide rows (there are at most V of them); reads
+// are coalesced along a word's row.  n_k must be zero on entry.
+__global__ __launch_bounds__(256) void topic_totals_from_rows_kernel(PhiView phi, int32_t V, int32_t n_wide,
                                                                      int32_t K, int32_t words_per_slice,
                                                                      int32_t* n_k) {
     const int k = (int)(blockIdx.x * 256 + threadIdx.x);
     if (k >= K) return;
     const int v0 = (int)blockIdx.y * words_per_slice;
-    const int v1 = min(v0 + words_per_slice, V);
     int acc = 0;
-    for (int v = v0; v < v1; ++v) acc += n_wk[(size_t)v * (size_t)K + k];
+    for (int v = v0; v < min(v0 + words_per_slice, V); ++v) acc += (int)phi.narrow[(size_t)v * (size_t)K + k];
+    for (int r = v0; r < min(v0 + words_per_slice, n_wide); ++r) acc += phi.wide[(size_t)r * (size_t)K + k];
     if (acc != 0) atomicAdd(&n_k[k], acc);
 }
 
@@ -516,9 +536,12 @@ __global__ void to_word_major_kernel(const uint16_t* z_doc, const int32_t* tok_i
 // ------------------------------------------------------------------ log-likelihood kernels
 
 // Word side: sum over all cells of lgG(n_wk + beta) - lgG(beta), plus the topic totals' term.
-// Cells are read four at a time; the table of small counts comes ready-made from global
-// memory (lg_table: kLgTable entries, then lgG(beta)), larger counts use Stirling's series.
-__global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_wk, int64_t n_cells,
+// The 16-bit cells are read eight at a time, the 32-bit cells of the wide rows four at a time
+// (empty cells add nothing, so the unused 16-bit rows of the wide words do not matter); the
+// table of small counts comes ready-made from global memory (lg_table: kLgTable entries, then
+// lgG(beta)), larger counts use Stirling's series.
+__global__ __launch_bounds__(256) void loglik_word_side_kernel(PhiView phi, int64_t n_narrow_cells,
+                                                               int64_t n_wide_cells,
                                                                const int32_t* n_k, int32_t K,
                                                                double beta, double v_beta,
                                                                const double* lg_table,
@@ -534,28 +557,45 @@ __global__ __launch_bounds__(256) void loglik_word_side_kernel(const int32_t* n_
             if (c >= kLgTable) acc += lgamma_large((double)c + beta) - lg_beta;
         }
     };
-    const int64_t n_quads = n_cells / 4, stride = (int64_t)gridDim.x * blockDim.x;
-    const int4* quads = reinterpret_cast<const int4*>(n_wk);
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n_quads; i += 4 * stride) {        // four loads in flight per thread
-        const int4 v0 = quads[i], v1 = quads[i + stride], v2 = quads[i + 2 * stride],
-                   v3 = quads[i + 3 * stride];
-        if (__ballot((v0.x | v0.y | v0.z | v0.w | v1.x | v1.y | v1.z | v1.w | v2.x | v2.y | v2.z | v2.w |
-                      v3.x | v3.y | v3.z | v3.w) != 0) == 0)
-            continue;
-        add_cell(v0.x); add_cell(v0.y); add_cell(v0.z); add_cell(v0.w);
-        add_cell(v1.x); add_cell(v1.y); add_cell(v1.z); add_cell(v1.w);
-        add_cell(v2.x); add_cell(v2.y); add_cell(v2.z); add_cell(v2.w);
-        add_cell(v3.x); add_cell(v3.y); add_cell(v3.z); add_cell(v3.w);
+    auto add_pair = [&](uint32_t two) { add_cell((int)(two & 0xffffu)); add_cell((int)(two >> 16)); };
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    {
+        const int64_t n_octs = n_narrow_cells / 8;
+        const uint4* octs = reinterpret_cast<const uint4*>(phi.narrow);
+        int64_t i = first;
+        for (; i + 3 * stride < n_octs; i += 4 * stride) {     // four loads in flight per thread
+            const uint4 v0 = octs[i], v1 = octs[i + stride], v2 = octs[i + 2 * stride],
+                        v3 = octs[i + 3 * stride];
+            if (__ballot((v0.x | v0.y | v0.z | v0.w | v1.x | v1.y | v1.z | v1.w | v2.x | v2.y | v2.z | v2.w |
+                          v3.x | v3.y | v3.z | v3.w) != 0) == 0)
+                continue;
+            add_pair(v0.x); add_pair(v0.y); add_pair(v0.z); add_pair(v0.w);
+            add_pair(v1.x); add_pair(v1.y); add_pair(v1.z); add_pair(v1.w);
+            add_pair(v2.x); add_pair(v2.y); add_pair(v2.z); add_pair(v2.w);
+            add_pair(v3.x); add_pair(v3.y); add_pair(v3.z); add_pair(v3.w);
+        }
+        for (; i < n_octs; i += stride) {
+            const uint4 v = octs[i];
+            if (__ballot((v.x | v.y | v.z | v.w) != 0) == 0) continue;
+            add_pair(v.x); add_pair(v.y); add_pair(v.z); add_pair(v.w);
+        }
     }
-    for (; i < n_quads; i += stride) {
-        const int4 v = quads[i];
-        if (__ballot((v.x | v.y | v.z | v.w) != 0) == 0) continue;
-        add_cell(v.x); add_cell(v.y); add_cell(v.z); add_cell(v.w);
+    {
+        const int64_t n_quads = n_wide_cells / 4;
+        const int4* quads = reinterpret_cast<const int4*>(phi.wide);
+        for (int64_t i = first; i < n_quads; i += stride) {
+            const int4 v = quads[i];
+            if (__ballot((v.x | v.y | v.z | v.w) != 0) == 0) continue;
+            add_cell(v.x); add_cell(v.y); add_cell(v.z); add_cell(v.w);
+        }
     }
     if (blockIdx.x == 0) {
-        const int64_t i = 4 * n_quads + (int64_t)threadIdx.x;      // up to three cells are left
-        add_cell(i < n_cells ? n_wk[i] : 0);
+        // up to seven 16-bit cells and up to three 32-bit cells are left
+        const int64_t i = n_narrow_cells / 8 * 8 + (int64_t)threadIdx.x;
+        add_cell(i < n_narrow_cells ? (int)phi.narrow[i] : 0);
+        const int64_t j = n_wide_cells / 4 * 4 + (int64_t)threadIdx.x;
+        add_cell(j < n_wide_cells ? phi.wide[j] : 0);
         const double lg_vb = lgamma(v_beta);
         for (int k = (int)threadIdx.x; k < K; k += (int)blockDim.x)
             acc += lg_vb - lgamma((double)n_k[k] + v_beta);

@@ -38,6 +38,17 @@ struct Tile {          // consecutive word-major tokens of one word
     int32_t whole;     // 1 if the tile holds every token of its word
 };
 
+// phi (Section 6.1.3: short integers for the dense model).  A word with fewer than 2^16 tokens
+// can never overflow a 16-bit count: its row lives in `narrow`.  The few heavier words have an
+// int32 row in `wide` (wide_row[v] = its index there, -1 for the others) and their rows in
+// `narrow` stay zero, so that sums over all cells of both matrices count every token once.
+constexpr int kNarrowWordLimit = 1 << 16;   // tokens of a word from which its row is wide
+struct PhiView {
+    uint16_t* narrow;           // [V][K]
+    int32_t* wide;              // [n_wide][K]
+    const int32_t* wide_row;    // [V]
+};
+
 struct SampleArgs {
     const Tile* tiles;
     const uint32_t* tok_slot;   // [T] slot of the theta row of each word-major token's document
@@ -48,7 +59,7 @@ struct SampleArgs {
     // whose first word is the row's length, then holds the entries in one of the two layouts
     // below (SplitRows / PackedRows); padding entries hold count 0 and topic K
     const unsigned char* slots;
-    const int32_t* n_wk;        // [V][K]
+    PhiView phi;
     const int32_t* n_k;         // [K]
     int32_t K, Kpad;            // Kpad = K+1 rounded up to a multiple of the dense group: p*(K..Kpad-1) = 0
     double alpha, beta, beta_V;
@@ -409,13 +420,29 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     tl.word = __builtin_amdgcn_readfirstlane(tl.word);
     tl.begin = __builtin_amdgcn_readfirstlane(tl.begin);
     tl.count = __builtin_amdgcn_readfirstlane(tl.count);
-    const int32_t* phi_v = a.n_wk + (size_t)tl.word * (size_t)K;
+    // the word's row of phi: 16-bit or 32-bit cells, the same for the whole workgroup
+    const int wide_row = __builtin_amdgcn_readfirstlane(a.phi.wide_row[tl.word]);
+    const bool wide = wide_row >= 0;
+    const unsigned char* phi_cells = wide ? reinterpret_cast<const unsigned char*>(a.phi.wide)
+                                          : reinterpret_cast<const unsigned char*>(a.phi.narrow);
+    const size_t phi_cell0 = (size_t)(wide ? wide_row : tl.word) * (size_t)K;
+    const uint32_t phi_shift = wide ? 2u : 1u, phi_mask = wide ? 0xffffffffu : 0xffffu;
 
     // ---- stage p*(k) = (phi_kv + beta)/(n_k + beta V) as fp32 (Eq. 8)
-    for (int k = tid; k < Kpad; k += kWaves * kWave) {
-        float w = 0.f;
-        if (k < K) w = (float)(((double)phi_v[k] + a.beta) / ((double)a.n_k[k] + a.beta_V));
-        pstar[k] = w;
+    if (wide) {
+        const int32_t* phi_v = reinterpret_cast<const int32_t*>(phi_cells) + phi_cell0;
+        for (int k = tid; k < Kpad; k += kWaves * kWave) {
+            float w = 0.f;
+            if (k < K) w = (float)(((double)phi_v[k] + a.beta) / ((double)a.n_k[k] + a.beta_V));
+            pstar[k] = w;
+        }
+    } else {
+        const uint16_t* phi_v = reinterpret_cast<const uint16_t*>(phi_cells) + phi_cell0;
+        for (int k = tid; k < Kpad; k += kWaves * kWave) {
+            float w = 0.f;
+            if (k < K) w = (float)(((double)phi_v[k] + a.beta) / ((double)a.n_k[k] + a.beta_V));
+            pstar[k] = w;
+        }
     }
     __syncthreads();
     for (int g = tid; g < ng; g += kWaves * kWave) {
@@ -463,7 +490,11 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             mine.nnz = *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
             mine.u = token_uniform(a.seed, a.iter, id);
             // the token itself is taken out of phi and n_k at its own topic
-            mine.w_o = (float)(((double)(phi_v[mine.o] - 1) + a.beta) /
+            // (its cell of phi, of either width, is cut out of the aligned dword that holds it)
+            const size_t own_byte = (phi_cell0 + (size_t)mine.o) << phi_shift;
+            const uint32_t own_dword = *reinterpret_cast<const uint32_t*>(phi_cells + (own_byte & ~(size_t)3));
+            const int32_t phi_own = (int32_t)((own_dword >> (((uint32_t)own_byte & 2u) << 3)) & phi_mask);
+            mine.w_o = (float)(((double)(phi_own - 1) + a.beta) /
                                ((double)(a.n_k[mine.o] - 1) + a.beta_V));
             delta = (double)mine.w_o - (double)pstar[mine.o];
             // cp[ng - 1] = sum_k p*(k), read from LDS where it is needed; Q = alpha sum (Eq. 7)

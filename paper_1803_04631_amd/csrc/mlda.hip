@@ -119,17 +119,26 @@ ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
 }
 
 // The model and the scratch of the reductions.
+// phi[i] is one copy of the model: the 16-bit matrix [V][K], then room for the int32 rows of
+// the words with 2^16 tokens or more, of which a corpus of T tokens has at most T / 2^16.
 struct ModelLayout {
-    size_t n_wk[2] = {0, 0}, n_k[2] = {0, 0}, ll_partial = 0, ll_scalars = 0, lg_table = 0, row_entries = 0,
-           total = 0;
+    size_t phi[2] = {0, 0}, phi_wide = 0, phi_bytes = 0, wide_row = 0, n_k[2] = {0, 0}, ll_partial = 0,
+           ll_scalars = 0, lg_table = 0, row_entries = 0, total = 0;
 };
 
-ModelLayout model_layout(int32_t V, int32_t K, bool two_phi) {
+int64_t wide_rows_bound(int32_t V, int64_t T) {
+    return std::min<int64_t>((int64_t)V, T / mlda::kNarrowWordLimit);
+}
+
+ModelLayout model_layout(int32_t V, int32_t K, int64_t T, bool two_phi) {
     ModelLayout L;
     size_t at = 0;
     auto put = [&](size_t bytes) { const size_t o = at; at += align_up(bytes, kAlign); return o; };
-    L.n_wk[0] = put((size_t)V * (size_t)K * 4);
-    L.n_wk[1] = two_phi ? put((size_t)V * (size_t)K * 4) : L.n_wk[0];
+    L.phi_wide = align_up((size_t)V * (size_t)K * 2, kAlign);      // offset of the wide rows inside a copy
+    L.phi_bytes = L.phi_wide + align_up((size_t)wide_rows_bound(V, T) * (size_t)K * 4, kAlign);
+    L.phi[0] = put(L.phi_bytes);
+    L.phi[1] = two_phi ? put(L.phi_bytes) : L.phi[0];
+    L.wide_row = put((size_t)V * 4);
     L.n_k[0] = put((size_t)K * 4);
     L.n_k[1] = two_phi ? put((size_t)K * 4) : L.n_k[0];
     L.ll_partial = put((size_t)(2 * kLoglikBlocks + kMaxThetaGrid) * 8);
@@ -157,6 +166,7 @@ struct HostChunk {
     bool packed = true;                 // theta rows as 4-byte entries (no document has 2^14 tokens)
     size_t slots_bytes = 0;
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
+    int32_t n_wide_tiles = 0;           // sampling tiles of words whose row of phi is int32
     ChunkLayout L;
     unsigned char* arena = nullptr;     // L.static_bytes bytes
     bool pinned = false;
@@ -382,7 +392,10 @@ struct mlda_ctx {
     hipStream_t stream = nullptr;
     int n_cus = 0, lds_limit = 0;
     size_t sample_lds = 0;
-    int32_t* n_wk[2] = {nullptr, nullptr};   // [model_cur] is the current phi; two buffers when streamed
+    mlda::PhiView phi[2];                // [model_cur] is the current phi; two copies when streamed
+    size_t phi_bytes = 0;                // bytes of one copy
+    int32_t n_wide = 0;                  // words with an int32 row
+    std::vector<int32_t> wide_row;       // [V] host copy of phi[].wide_row
     int32_t* n_k[2] = {nullptr, nullptr};
     int model_cur = 0;
     double *ll_partial = nullptr, *ll_scalars = nullptr;   // scalars: value, theta sum, document term
@@ -424,7 +437,7 @@ struct mlda_ctx {
     size_t slots_bytes = 0;
     mlda::Tile* tiles = nullptr;         // sampling tiles
     mlda::Tile* segs = nullptr;          // phi rebuild segments
-    int32_t n_tiles = 0, n_segs = 0, n_split = 0;
+    int32_t n_tiles = 0, n_segs = 0, n_split = 0, n_wide_tiles = 0;
 };
 
 namespace {
@@ -444,6 +457,7 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->packed = h.packed;
     c->slots_bytes = h.slots_bytes;
     c->n_tiles = h.n_tiles; c->n_segs = h.n_segs; c->n_split = h.n_split;
+    c->n_wide_tiles = h.n_wide_tiles;
     c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
     c->tok_id = (int32_t*)(base + h.L.tok_id);
     c->doc_map = (int32_t*)(base + h.L.doc_map);
@@ -556,14 +570,14 @@ int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
         if (c->n_split > 0) {
             dim3 grid((unsigned)c->n_split, (unsigned)blocks_for(c->K, 256));
             hipLaunchKernelGGL(zero_rows_kernel, grid, dim3(256), 0, c->stream, c->split_words,
-                               c->n_wk[which], c->K);
+                               c->phi[which], c->K);
         }
         hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks_for(c->K, 256)), dim3(256), 0, c->stream,
                            c->n_k[which], (int64_t)c->K, 0);
     }
     if (c->n_tiles > 0) {
         hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes, c->stream,
-                           c->segs, z, c->n_wk[which], c->K);
+                           c->segs, z, c->phi[which], c->K);
         if (c->streamed) {
             // n_k after the last chunk
         } else if ((int64_t)c->V * c->K * 2 < c->T) {
@@ -571,7 +585,7 @@ int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
             const int words_per_slice = 64;
             dim3 grid((unsigned)blocks_for(c->K, 256), (unsigned)blocks_for(c->V, words_per_slice));
             hipLaunchKernelGGL(topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream,
-                               c->n_wk[which], c->V, c->K, words_per_slice, c->n_k[which]);
+                               c->phi[which], c->V, c->n_wide, c->K, words_per_slice, c->n_k[which]);
         } else {
             const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
             hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes, c->stream,
@@ -583,9 +597,9 @@ int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
 
 // Streamed: phi[which] starts at zero before the first chunk adds to it ...
 int begin_model(mlda_ctx* c, int which) {
-    const int64_t cells = (int64_t)c->V * c->K;
-    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
-                       c->n_wk[which], cells, 0);
+    const int64_t dwords = (int64_t)(c->phi_bytes / 4);
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(dwords, 256)), dim3(256), 0, c->stream,
+                       (int32_t*)c->phi[which].narrow, dwords, 0);
     return launch_check("fill_i32_kernel");
 }
 
@@ -595,8 +609,8 @@ int finish_model(mlda_ctx* c, int which) {
                        c->n_k[which], (int64_t)c->K, 0);
     const int words_per_slice = 64;
     dim3 grid((unsigned)blocks_for(c->K, 256), (unsigned)blocks_for(c->V, words_per_slice));
-    hipLaunchKernelGGL(mlda::topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream, c->n_wk[which],
-                       c->V, c->K, words_per_slice, c->n_k[which]);
+    hipLaunchKernelGGL(mlda::topic_totals_from_rows_kernel, grid, dim3(256), 0, c->stream, c->phi[which],
+                       c->V, c->n_wide, c->K, words_per_slice, c->n_k[which]);
     return launch_check("topic totals");
 }
 
@@ -640,7 +654,7 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     a.z_cur = z_cur;
     a.z_next = z_next;
     a.slots = c->slots;
-    a.n_wk = c->n_wk[c->model_cur];
+    a.phi = c->phi[c->model_cur];
     a.n_k = c->n_k[c->model_cur];
     a.K = c->K;
     a.Kpad = c->Kpad;
@@ -660,9 +674,9 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
 // left by the last rebuild_theta.
 int launch_loglik(mlda_ctx* c) {
     using namespace mlda;
-    const int64_t cells = (int64_t)c->V * c->K;
     hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
-                       c->n_wk[c->model_cur], cells, c->n_k[c->model_cur], c->K, c->beta,
+                       c->phi[c->model_cur], (int64_t)c->V * c->K, (int64_t)c->n_wide * c->K,
+                       c->n_k[c->model_cur], c->K, c->beta,
                        (double)c->V * c->beta, c->lg_table_beta, c->ll_partial);
     hipLaunchKernelGGL(loglik_doc_term_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream, c->doc_ptr,
                        c->D, (double)c->K * c->alpha, c->ll_partial + kLoglikBlocks);
@@ -684,9 +698,9 @@ int add_theta_loglik(mlda_ctx* c, bool first) {
 // the corpus, scalars[2]).
 int finish_loglik_streamed(mlda_ctx* c) {
     using namespace mlda;
-    const int64_t cells = (int64_t)c->V * c->K;
     hipLaunchKernelGGL(loglik_word_side_kernel, dim3(kLoglikBlocks), dim3(256), 0, c->stream,
-                       c->n_wk[c->model_cur], cells, c->n_k[c->model_cur], c->K, c->beta,
+                       c->phi[c->model_cur], (int64_t)c->V * c->K, (int64_t)c->n_wide * c->K,
+                       c->n_k[c->model_cur], c->K, c->beta,
                        (double)c->V * c->beta, c->lg_table_beta, c->ll_partial);
     hipLaunchKernelGGL(loglik_final_kernel, dim3(1), dim3(256), 0, c->stream, c->ll_partial, kLoglikBlocks,
                        (const double*)(c->ll_scalars + 1), 0, c->ll_scalars);
@@ -740,14 +754,20 @@ size_t streamed_workspace_bound(const int64_t* doc_ptr, int64_t D, int32_t V, in
         const int64_t a = chunk_first(doc_ptr, D, M, m), b = chunk_first(doc_ptr, D, M, m + 1);
         chunk = std::max(chunk, chunk_layout_bound(b - a, doc_ptr[b] - doc_ptr[a], V, K).total);
     }
-    return model_layout(V, K, true).total + 2 * chunk;
+    return model_layout(V, K, doc_ptr[D], true).total + 2 * chunk;
 }
 
 // Everything mlda_create and mlda_create_streamed share: device limits, the model's buffers
 // and tables.  `chunks` are prepared; `base` is the workspace.
 int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
-    c->n_wk[0] = (int32_t*)(base + ML.n_wk[0]);
-    c->n_wk[1] = (int32_t*)(base + ML.n_wk[1]);
+    for (int i = 0; i < 2; ++i) {
+        c->phi[i].narrow = (uint16_t*)(base + ML.phi[i]);
+        c->phi[i].wide = (int32_t*)(base + ML.phi[i] + ML.phi_wide);
+        c->phi[i].wide_row = (const int32_t*)(base + ML.wide_row);
+    }
+    c->phi_bytes = ML.phi_bytes;
+    HIP_TRY(hipMemcpyAsync(base + ML.wide_row, c->wide_row.data(), (size_t)c->V * 4, hipMemcpyHostToDevice,
+                           c->stream));
     c->n_k[0] = (int32_t*)(base + ML.n_k[0]);
     c->n_k[1] = (int32_t*)(base + ML.n_k[1]);
     c->ll_partial = (double*)(base + ML.ll_partial);
@@ -761,9 +781,9 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
                        c->stream, c->lg_table_beta, c->beta);
     // rows of words without tokens are never written again: start phi at zero
-    const int64_t cells = (int64_t)c->V * c->K;
-    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(cells, 256)), dim3(256), 0, c->stream,
-                       c->n_wk[0], cells, 0);
+    const int64_t dwords = (int64_t)(c->phi_bytes / 4);
+    hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(dwords, 256)), dim3(256), 0, c->stream,
+                       (int32_t*)c->phi[0].narrow, dwords, 0);
     RC_TRY(launch_check("model set-up kernels"));
     const void* samplers[] = {sample_kernel_for(c->K, true), sample_kernel_for(c->K, false)};
     if (c->sample_lds > 48 * 1024)
@@ -782,6 +802,43 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
                                     (int)mlda::theta_lds_bytes(c->K, false)));
     }
     return MLDA_OK;
+}
+
+// Which words get an int32 row of phi: those with 2^16 tokens or more in the whole corpus.
+int find_wide_rows(mlda_ctx* c, const int32_t* word_ids) {
+    try {
+        const int n_parts = (int)std::max<int64_t>(1, std::min<int64_t>(8, c->T_all >> 22));
+        std::vector<std::vector<int32_t>> hist((size_t)n_parts);
+        const int64_t per = (c->T_all + n_parts - 1) / n_parts;
+        bool bad = false;
+        parallel_chunks(n_parts, [&](int p) {
+            try { hist[(size_t)p].assign((size_t)c->V, 0); } catch (const std::bad_alloc&) { bad = true; return; }
+            auto& h = hist[(size_t)p];
+            const int32_t V = c->V;
+            for (int64_t t = per * p; t < std::min(c->T_all, per * (p + 1)); ++t) {
+                const int32_t w = word_ids[t];
+                if (w >= 0 && w < V) h[(size_t)w] += 1;      // (ids out of range are reported later)
+            }
+        });
+        if (bad) return fail(MLDA_ENOMEM, "out of host memory");
+        c->wide_row.assign((size_t)c->V, -1);
+        c->n_wide = 0;
+        for (int32_t v = 0; v < c->V; ++v) {
+            int64_t n = 0;
+            for (int p = 0; p < n_parts; ++p) n += hist[(size_t)p][(size_t)v];
+            if (n >= mlda::kNarrowWordLimit) c->wide_row[(size_t)v] = c->n_wide++;
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(MLDA_ENOMEM, "out of host memory");
+    }
+    return MLDA_OK;
+}
+
+void count_wide_tiles(const mlda_ctx* c, HostChunk& h) {
+    const mlda::Tile* tiles = (const mlda::Tile*)(h.arena + h.L.tiles);
+    h.n_wide_tiles = 0;
+    for (int32_t i = 0; i < h.n_tiles; ++i)
+        if (c->wide_row[(size_t)tiles[i].word] >= 0) h.n_wide_tiles += 1;
 }
 
 int device_limits(mlda_ctx* c) {
@@ -925,7 +982,7 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
     if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
     if (D < 0 || T < 0 || V < 1 || K < 1 || K > 65535 || T >= ((int64_t)1 << 31))
         return fail(MLDA_EINVAL, "need D >= 0, 0 <= T < 2^31, V >= 1, 1 <= K <= 65535");
-    *bytes = model_layout(V, K, false).total + chunk_layout_bound(D, T, V, K).total;
+    *bytes = model_layout(V, K, T, false).total + chunk_layout_bound(D, T, V, K).total;
     return MLDA_OK;
 }
 
@@ -954,11 +1011,13 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     c->alpha = alpha; c->beta = beta; c->seed = seed;
     c->stream = (hipStream_t)hip_stream;
     int rc = device_limits(c);
+    if (rc == MLDA_OK) rc = find_wide_rows(c, word_ids);
     if (rc == MLDA_OK) {
         try { c->chunks = std::vector<HostChunk>(1); } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
     }
     if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->chunks[0]);
-    const ModelLayout ML = model_layout(V, K, false);
+    if (rc == MLDA_OK) count_wide_tiles(c, c->chunks[0]);
+    const ModelLayout ML = model_layout(V, K, T, false);
     if (rc == MLDA_OK && ML.total + c->chunks[0].L.total > workspace_bytes)
         rc = fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
                                    std::to_string(ML.total + c->chunks[0].L.total));
@@ -1000,6 +1059,7 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     c->stream = (hipStream_t)hip_stream;
     c->streamed = true;
     int rc = device_limits(c);
+    if (rc == MLDA_OK) rc = find_wide_rows(c, word_ids);
     if (rc == MLDA_OK) {
         try {
             c->chunks = std::vector<HostChunk>((size_t)n_chunks);
@@ -1010,9 +1070,10 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     for (int32_t m = 0; rc == MLDA_OK && m < n_chunks; ++m) {
         rc = prepare_chunk(doc_ptr, word_ids, chunk_first(doc_ptr, D, n_chunks, m),
                            chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, c->chunks[(size_t)m]);
+        if (rc == MLDA_OK) count_wide_tiles(c, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) chunk_bytes = std::max(chunk_bytes, c->chunks[(size_t)m].L.total);
     }
-    const ModelLayout ML = model_layout(V, K, true);
+    const ModelLayout ML = model_layout(V, K, T, true);
     if (rc == MLDA_OK && ML.total + 2 * chunk_bytes > workspace_bytes)
         rc = fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
                                    std::to_string(ML.total + 2 * chunk_bytes));
@@ -1200,9 +1261,23 @@ int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
 int mlda_get_word_topic(mlda_ctx* c, int32_t* n_wk) {
     RC_TRY(need_state(c));
     if (!n_wk) return fail(MLDA_EINVAL, "n_wk is null");
-    HIP_TRY(hipMemcpyAsync(n_wk, c->n_wk[c->model_cur], (size_t)c->V * c->K * 4, hipMemcpyDeviceToHost,
-                           c->stream));
+    // the 16-bit matrix and the wide rows are fetched as they are and widened here
+    const size_t cells = (size_t)c->V * (size_t)c->K, wide_cells = (size_t)c->n_wide * (size_t)c->K;
+    std::vector<uint16_t> narrow;
+    std::vector<int32_t> wide;
+    try { narrow.resize(cells); wide.resize(wide_cells); }
+    catch (const std::bad_alloc&) { return fail(MLDA_ENOMEM, "out of host memory"); }
+    const mlda::PhiView& phi = c->phi[c->model_cur];
+    HIP_TRY(hipMemcpyAsync(narrow.data(), phi.narrow, cells * 2, hipMemcpyDeviceToHost, c->stream));
+    if (wide_cells > 0)
+        HIP_TRY(hipMemcpyAsync(wide.data(), phi.wide, wide_cells * 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
+    for (int32_t v = 0; v < c->V; ++v) {
+        const int32_t r = c->wide_row[(size_t)v];
+        int32_t* row = n_wk + (size_t)v * (size_t)c->K;
+        if (r >= 0) std::memcpy(row, wide.data() + (size_t)r * (size_t)c->K, (size_t)c->K * 4);
+        else for (int32_t k = 0; k < c->K; ++k) row[k] = narrow[(size_t)v * (size_t)c->K + (size_t)k];
+    }
     return MLDA_OK;
 }
 
@@ -1304,8 +1379,9 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
         const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
         // per token: row slot 4, token id 4, old topic 2, new topic 2, row length 4
+        // per tile: the word's row of phi, 2 K bytes, or 4 K for a word with 2^16 tokens or more
         bytes[i] = 16.0 * (double)c->T + (c->packed ? 4.0 : 6.0) * row_entries +
-                   4.0 * (double)c->K * (double)c->n_tiles;
+                   (double)c->K * (2.0 * (double)c->n_tiles + 2.0 * (double)c->n_wide_tiles);
     }
     *n_iters = n;
     return MLDA_OK;

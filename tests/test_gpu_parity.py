@@ -262,6 +262,39 @@ def test_streamed_edge_cases(mlda):
     empty.close()
 
 
+def test_phi_cell_widths(mlda):
+    """phi keeps 16-bit cells for words with fewer than 2^16 tokens and int32 rows for the
+    others: words with 65535, 65536 and 70001 tokens, every token of a word on one topic (the
+    largest value a 16-bit cell can take, and the first that needs the wide row), an odd K so
+    that rows start in the middle of a dword; resident and streamed (cells added to by
+    several chunks)."""
+    V, K, alpha, beta = 5, 7, 0.5, 0.01
+    word_counts = np.array([65535, 65536, 70001, 10, 0])
+    rng = np.random.default_rng(5)
+    word_ids = rng.permutation(np.repeat(np.arange(V, dtype=np.int32), word_counts))
+    T = len(word_ids)
+    lens = rng.multinomial(T, np.ones(400) / 400).astype(np.int64)
+
+    class C:
+        pass
+    c = C(); c.word_ids = word_ids; c.T = T
+    c.doc_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    z_one = (c.word_ids % K).astype(np.uint16)              # word v entirely on topic v
+    for chunks in (1, 3):
+        say("phi cell widths, chunks", chunks)
+        model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, SEED, chunks=chunks)
+        model.set_assignments(z_one, it=0)
+        n_wk, _ = check_counts(model, c, z_one, V, K)
+        assert n_wk[0, 0] == 65535 and n_wk[1, 1] == 65536 and n_wk[2, 2] == 70001
+        n_wk, n_k = oracle.count_word_topic(c.word_ids, z_one, V, K)
+        ll = oracle.loglik(c.doc_ptr, z_one, V, K, alpha, beta, n_wk, n_k)
+        assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
+        z = z_one
+        for it in (1, 2):
+            z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
+        model.close()
+
+
 def test_empty_corpus(mlda):
     doc_ptr = np.zeros(4, dtype=np.int64)
     model = mlda.Mlda(doc_ptr, np.zeros(0, dtype=np.int32), 5, 3, 0.5, 0.01, 1)
@@ -315,7 +348,9 @@ def test_step_with_loglik_flag_and_timing(mlda):
     assert model.loglik() > ll0
     # the algorithmic byte count of each launch follows its definition: the state a launch
     # samples from is the one before it
-    n_tiles = int(np.ceil(np.bincount(c.word_ids, minlength=cfg.V) / 1024).sum())
+    per_word = np.bincount(c.word_ids, minlength=cfg.V)
+    n_tiles = int(np.ceil(per_word / 1024).sum())
+    n_wide_tiles = int(np.ceil(per_word[per_word >= 2**16] / 1024).sum())   # int32 rows of phi
     lens = np.diff(c.doc_ptr)
     before = oracle.doc_topic_csr(c.doc_ptr, model.assignments(), cfg.K)[0]
     model.step(2)
@@ -325,7 +360,8 @@ def test_step_with_loglik_flag_and_timing(mlda):
     got = model.sampler_bytes()
     for row_ptr, b in zip((before, mid), got):
         entry_bytes = 4.0 if lens.max() < 2**14 else 6.0       # packed theta entries when counts fit 14 bits
-        want = 16.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum()) + 4.0 * cfg.K * n_tiles
+        want = (16.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum())
+                + cfg.K * (2.0 * n_tiles + 2.0 * n_wide_tiles))
         assert b == want
     assert len(got) == 2
     model.close()
