@@ -34,13 +34,27 @@ def say(*a):
 
 @pytest.mark.parametrize("name,n_listed", [("C4", 20000), ("C3", 8000), ("C5", 2500)])
 def test_first_iteration_at_full_size(name, n_listed):
+    cfg = corpus_synth.CONFIGS[name]
+    check_first_iteration(name, cfg, corpus_synth.generate(cfg), n_listed)
+
+
+def test_first_iteration_near_the_token_limit():
+    """The library takes fewer than 2^31 tokens: C4's shape with 2.85 times its documents,
+    2.1e9 tokens (98 % of the limit), so that token positions, byte offsets beyond 2^32 and
+    the slot offsets of 23 million theta rows are exercised near the top of their ranges."""
+    cfg = corpus_synth.CONFIGS["C4"]
+    c = corpus_synth.generate(cfg, scale=2.85)
+    assert 2.05e9 < c.T < 2**31
+    check_first_iteration("C4x2.85", cfg, c, 20000)
+
+
+def check_first_iteration(name, cfg, c, n_listed):
     import torch
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible")
     import paper_1803_04631_amd as mlda
-    cfg = corpus_synth.CONFIGS[name]
-    c = corpus_synth.generate(cfg)
     T, V, K = c.T, cfg.V, cfg.K
+    D = len(c.doc_ptr) - 1
     say(name, "generated, T =", T)
     model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, cfg.alpha, cfg.beta, SEED)
     model.init_random()
@@ -91,7 +105,7 @@ def test_first_iteration_at_full_size(name, n_listed):
     row_sum = np.add.reduceat(counts.astype(np.int64), np.minimum(row_ptr[:-1], len(counts) - 1))
     assert np.array_equal(row_sum[lens > 0], lens[lens > 0])               # Eq. 5
     assert counts.min() > 0 and int(topics.max()) < K
-    for d in np.concatenate([rng.integers(cfg.D, size=300), [0, cfg.D - 1, np.argmax(lens)]]):
+    for d in np.concatenate([rng.integers(D, size=300), [0, D - 1, np.argmax(lens)]]):
         row = np.bincount(z1[c.doc_ptr[d]:c.doc_ptr[d + 1]], minlength=K)
         t = topics[row_ptr[d]:row_ptr[d + 1]]
         assert np.array_equal(t, np.flatnonzero(row)) and np.array_equal(counts[row_ptr[d]:row_ptr[d + 1]], row[t])
@@ -103,7 +117,7 @@ def test_first_iteration_at_full_size(name, n_listed):
     nz = n_wk1[n_wk1 > 0].astype(np.float64)
     ll = (K * gammaln(V * cfg.beta) - gammaln(n_k1 + V * cfg.beta).sum()
           + (gammaln(nz + cfg.beta) - gammaln(cfg.beta)).sum()
-          + cfg.D * gammaln(K * cfg.alpha) - gammaln(lens + K * cfg.alpha).sum()
+          + D * gammaln(K * cfg.alpha) - gammaln(lens + K * cfg.alpha).sum()
           + (gammaln(counts + cfg.alpha) - gammaln(cfg.alpha)).sum())
     assert abs(model.loglik() - ll) <= 1e-5 * abs(ll)
     say(name, "log-likelihood agrees")
