@@ -114,6 +114,7 @@ EDGE_CASES = [
     ("large_k_small_docs",  300, 2000, 10000, 120),   # C5-like K: 45 KB of LDS per tile
     ("short_docs",          3000, 200, 16,  1.2),     # many single-token documents (S = 0)
     ("k_twenty_thousand",   40,  300,  20000, 400),   # every kernel beyond 64 KB of LDS
+    ("k_near_lds_limit",    40,  300,  30800, 400),   # 160 KB of LDS: one workgroup per CU
     # documents of 2^14 tokens or more: the library falls back to 6-byte theta entries
     ("huge_docs_split_rows", 3,   400,  700, 17000),
     ("huge_docs_few_topics", 4,   50,   24,  16500),
