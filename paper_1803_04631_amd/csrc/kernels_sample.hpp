@@ -35,7 +35,8 @@ struct Tile {          // consecutive word-major tokens of one word
     int32_t word;
     int32_t begin;     // first word-major token position
     int32_t count;     // 1 .. tile size
-    int32_t whole;     // 1 if the tile holds every token of its word
+    int32_t whole;     // phi segments: 1 if the segment holds every token of its word;
+                       // sampling tiles: the word's row in PhiView::wide, or -1
 };
 
 // phi (Section 6.1.3: short integers for the dense model).  A word with fewer than 2^16 tokens
@@ -421,7 +422,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     tl.begin = __builtin_amdgcn_readfirstlane(tl.begin);
     tl.count = __builtin_amdgcn_readfirstlane(tl.count);
     // the word's row of phi: 16-bit or 32-bit cells, the same for the whole workgroup
-    const int wide_row = __builtin_amdgcn_readfirstlane(a.phi.wide_row[tl.word]);
+    const int wide_row = __builtin_amdgcn_readfirstlane(tl.whole);    // (kept in the tile: one load less in the chain)
     const bool wide = wide_row >= 0;
     const unsigned char* phi_cells = wide ? reinterpret_cast<const unsigned char*>(a.phi.wide)
                                           : reinterpret_cast<const unsigned char*>(a.phi.narrow);

@@ -342,7 +342,8 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
     size_t it = 0, is = 0, ip = 0;
     for (int32_t v = 0; v < V; ++v) {
         const int32_t n = word_ptr[v + 1] - word_ptr[v];
-        // `whole` carries the tile's index until the tiles are sorted
+        // a tile's `whole` carries its index until the tiles are sorted, then its word's wide row
+        // of phi (mark_wide_tiles)
         for (int32_t b = 0; b < n; b += tile, ++it)
             tiles[it] = mlda::Tile{v, word_ptr[v] + b, std::min(tile, n - b), (int32_t)it};
         if (!accumulate && n > kPhiSegment) split_words[ip++] = v;
@@ -360,10 +361,6 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         std::stable_sort(tiles, tiles + n_tiles, [&](const mlda::Tile& a, const mlda::Tile& b) {
             return tile_key[(size_t)a.whole] < tile_key[(size_t)b.whole];
         });
-        for (size_t i = 0; i < n_tiles; ++i) {
-            const int32_t n = word_ptr[tiles[i].word + 1] - word_ptr[tiles[i].word];
-            tiles[i].whole = n <= tile ? 1 : 0;
-        }
         std::stable_sort(segs, segs + n_segs,
                          [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
     } catch (const std::bad_alloc&) {
@@ -834,11 +831,14 @@ int find_wide_rows(mlda_ctx* c, const int32_t* word_ids) {
     return MLDA_OK;
 }
 
-void count_wide_tiles(const mlda_ctx* c, HostChunk& h) {
-    const mlda::Tile* tiles = (const mlda::Tile*)(h.arena + h.L.tiles);
+// Every sampling tile carries its word's row among the wide rows of phi (or -1).
+void mark_wide_tiles(const mlda_ctx* c, HostChunk& h) {
+    mlda::Tile* tiles = (mlda::Tile*)(h.arena + h.L.tiles);
     h.n_wide_tiles = 0;
-    for (int32_t i = 0; i < h.n_tiles; ++i)
-        if (c->wide_row[(size_t)tiles[i].word] >= 0) h.n_wide_tiles += 1;
+    for (int32_t i = 0; i < h.n_tiles; ++i) {
+        tiles[i].whole = c->wide_row[(size_t)tiles[i].word];
+        if (tiles[i].whole >= 0) h.n_wide_tiles += 1;
+    }
 }
 
 int device_limits(mlda_ctx* c) {
@@ -1016,7 +1016,7 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
         try { c->chunks = std::vector<HostChunk>(1); } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
     }
     if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->chunks[0]);
-    if (rc == MLDA_OK) count_wide_tiles(c, c->chunks[0]);
+    if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[0]);
     const ModelLayout ML = model_layout(V, K, T, false);
     if (rc == MLDA_OK && ML.total + c->chunks[0].L.total > workspace_bytes)
         rc = fail(MLDA_ENOMEM, "workspace has " + std::to_string(workspace_bytes) + " bytes, need " +
@@ -1070,7 +1070,7 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     for (int32_t m = 0; rc == MLDA_OK && m < n_chunks; ++m) {
         rc = prepare_chunk(doc_ptr, word_ids, chunk_first(doc_ptr, D, n_chunks, m),
                            chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, c->chunks[(size_t)m]);
-        if (rc == MLDA_OK) count_wide_tiles(c, c->chunks[(size_t)m]);
+        if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) chunk_bytes = std::max(chunk_bytes, c->chunks[(size_t)m].L.total);
     }
     const ModelLayout ML = model_layout(V, K, T, true);
