@@ -22,8 +22,11 @@ _CFLAGS = ["-O2", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fas
 
 
 def build(force: bool = False) -> str:
-    override = os.environ.get("LDA_ORACLE_LIB")     # the mutation test points at broken builds
-    if override:
+    # The mutation test binds deliberately broken builds in subprocesses of its own: the
+    # override counts only together with the marker that test sets, so that no other
+    # environment can swap the checker under the parity tests.
+    override = os.environ.get("LDA_ORACLE_LIB")
+    if override and os.environ.get("LDA_ORACLE_MUTATION_TEST") == "1":
         return override
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", *_CFLAGS, "-o", _LIB, _SRC, "-lm"])

@@ -79,7 +79,7 @@ void oracle_uniforms(uint64_t seed, uint32_t iter, uint64_t token0, int64_t n, d
     for (int64_t i = 0; i < n; ++i) u[i] = oracle_uniform(seed, iter, token0 + (uint64_t)i);
 }
 
-/* "Initially, each token is randomly assigned with a topic" (Section 2.1). */
+/* Random initial topics (Section 2.1): every token starts with a uniformly drawn topic. */
 void oracle_init_topics(int64_t T, int32_t K, uint64_t seed, uint16_t* z) {
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; ++t) {
@@ -216,25 +216,30 @@ void oracle_iteration(int64_t D, const int64_t* doc_ptr, const int32_t* word_ids
 /*
  * The same draw for a chosen list of tokens only (token index, document-major,
  * with the document of each given): lets a test check single outputs of a
- * corpus too large to pass over on the CPU.
+ * corpus too large to pass over on the CPU.  Listed tokens are independent, so
+ * they are spread over threads (each with its own dense row and work space).
  */
 void oracle_resample_listed(int64_t n_listed, const int64_t* token, const int64_t* doc,
                             const int64_t* doc_ptr, const int32_t* word_ids, const uint16_t* z,
                             int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
                             uint32_t iter, const int32_t* n_wk, const int32_t* n_k,
                             uint16_t* z_new) {
-    int32_t* n_d = (int32_t*)malloc(sizeof(int32_t) * (size_t)K);
-    double* work = (double*)malloc(sizeof(double) * 2 * (size_t)K);
-    for (int64_t i = 0; i < n_listed; ++i) {
-        const int64_t t = token[i], d = doc[i];
-        count_doc_row(z, doc_ptr[d], doc_ptr[d + 1], K, n_d);
-        const double u = oracle_uniform(seed, iter, (uint64_t)t);
-        z_new[i] = (uint16_t)oracle_resample_token(
-            K, V, alpha, beta, n_d, n_wk + (size_t)word_ids[t] * (size_t)K, n_k,
-            (int32_t)z[t], u, work, 0, 0);
+#pragma omp parallel
+    {
+        int32_t* row = (int32_t*)malloc(sizeof(int32_t) * (size_t)K);
+        double* scratch = (double*)malloc(sizeof(double) * 2 * (size_t)K);
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t i = 0; i < n_listed; ++i) {
+            const int64_t t = token[i], d = doc[i];
+            count_doc_row(z, doc_ptr[d], doc_ptr[d + 1], K, row);
+            const double u = oracle_uniform(seed, iter, (uint64_t)t);
+            const int32_t* n_w = n_wk + (size_t)word_ids[t] * (size_t)K;
+            z_new[i] = (uint16_t)oracle_resample_token(K, V, alpha, beta, row, n_w, n_k,
+                                                       (int32_t)z[t], u, scratch, 0, 0);
+        }
+        free(row);
+        free(scratch);
     }
-    free(n_d);
-    free(work);
 }
 
 /* -------------------------------------------------------- log-likelihood */

@@ -107,13 +107,16 @@ class Mlda:
     def __init__(self, doc_ptr, word_ids, V: int, K: int, alpha: float, beta: float, seed: int,
                  device: str = "cuda:0", chunks: int = 1):
         import torch
+        self.doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
+        word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
+        if len(self.doc_ptr) < 1 or self.doc_ptr[0] != 0 or int(self.doc_ptr[-1]) != len(word_ids):
+            raise ValueError("doc_ptr must start at 0 and end at len(word_ids): the library reads "
+                             "word_ids[0 .. doc_ptr[D])")
         self._lib = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("mlda needs a GPU: there is no CPU path")
         self._torch = torch
-        self.doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
-        word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
-        self.D, self.T, self.V, self.K = len(self.doc_ptr) - 1, len(word_ids), int(V), int(K)
+        self.D, self.T, self.V, self.K = len(self.doc_ptr) - 1, int(self.doc_ptr[-1]), int(V), int(K)
         self.alpha, self.beta, self.seed = float(alpha), float(beta), int(seed)
         self.device = torch.device(device)
         self.chunks = int(chunks)

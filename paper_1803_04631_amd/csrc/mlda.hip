@@ -149,12 +149,30 @@ ModelLayout model_layout(int32_t V, int32_t K, int64_t T, bool two_phi) {
     return L;
 }
 
+// body(0) .. body(n_chunks - 1), each on a thread of its own.  Nothing escapes a thread: an
+// exception inside a part (host memory running out) is caught there, every thread that was
+// started is joined, and the call returns false.  Parts whose thread could not be started
+// run on the calling thread.
 template <class F>
-void parallel_chunks(int n_chunks, F&& body) {
+bool parallel_chunks(int n_chunks, F&& body) {
     std::vector<std::thread> pool;
-    for (int c = 1; c < n_chunks; ++c) pool.emplace_back([&, c] { body(c); });
-    body(0);
+    std::vector<char> failed((size_t)std::max(n_chunks, 1), 0);
+    auto guarded = [&](int c) {
+        try { body(c); } catch (...) { failed[(size_t)c] = 1; }
+    };
+    int started = 1;
+    try {
+        pool.reserve((size_t)std::max(n_chunks - 1, 0));
+        for (; started < n_chunks; ++started) pool.emplace_back(guarded, started);
+    } catch (...) {
+        // no more threads (or no memory for them): the rest runs here, below
+    }
+    guarded(0);
+    for (int c = started; c < n_chunks; ++c) guarded(c);
     for (auto& t : pool) t.join();
+    for (char f : failed)
+        if (f) return false;
+    return true;
 }
 
 // Documents [d_begin, d_end) of the corpus, preprocessed: the static part of the chunk's
@@ -245,22 +263,19 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         const int64_t want = T / n_parts * p;
         return std::lower_bound(order_tokens.begin(), order_tokens.end(), want) - order_tokens.begin();
     };
-    try {
-        parallel_chunks(n_parts, [&](int p) {
-            auto& hist = part_hist[p];
-            hist.assign((size_t)V, 0);
-            for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
-                const int64_t d = doc_order[(size_t)i];
-                for (int64_t t = start_of(d); t < start_of(d) + len_of(d); ++t) {
-                    const int32_t w = word_ids[t];
-                    if (w < 0 || w >= V) { part_bad[p] = 1; return; }
-                    ++hist[w];
-                }
+    const bool counted = parallel_chunks(n_parts, [&](int p) {
+        auto& hist = part_hist[p];
+        hist.assign((size_t)V, 0);
+        for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
+            const int64_t d = doc_order[(size_t)i];
+            for (int64_t t = start_of(d); t < start_of(d) + len_of(d); ++t) {
+                const int32_t w = word_ids[t];
+                if (w < 0 || w >= V) { part_bad[p] = 1; return; }
+                ++hist[w];
             }
-        });
-    } catch (const std::bad_alloc&) {
-        return fail(MLDA_ENOMEM, "out of host memory");
-    }
+        }
+    });
+    if (!counted) return fail(MLDA_ENOMEM, "out of host memory");
     for (int p = 0; p < n_parts; ++p)
         if (part_bad[p]) return fail(MLDA_EINVAL, "word id outside [0, V)");
 
@@ -314,7 +329,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
     tile_base[0] = 0;
     for (int32_t v = 0; v < V; ++v)
         tile_base[v + 1] = tile_base[v] + (word_ptr[v + 1] - word_ptr[v] + tile - 1) / tile;
-    parallel_chunks(n_parts, [&](int p) {
+    const bool placed = parallel_chunks(n_parts, [&](int p) {
         auto& start = part_hist[p];
         for (int64_t i = part_lo(p); i < part_lo(p + 1); ++i) {
             const int64_t d = doc_order[(size_t)i];
@@ -329,6 +344,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
             }
         }
     });
+    if (!placed) return fail(MLDA_ENOMEM, "out of host memory");
     part_hist.clear();
 
     for (int64_t d = 0; d < D; ++d) doc_ptr32[d] = (int32_t)start_of(d);
@@ -807,9 +823,8 @@ int find_wide_rows(mlda_ctx* c, const int32_t* word_ids) {
         const int n_parts = (int)std::max<int64_t>(1, std::min<int64_t>(8, c->T_all >> 22));
         std::vector<std::vector<int32_t>> hist((size_t)n_parts);
         const int64_t per = (c->T_all + n_parts - 1) / n_parts;
-        bool bad = false;
-        parallel_chunks(n_parts, [&](int p) {
-            try { hist[(size_t)p].assign((size_t)c->V, 0); } catch (const std::bad_alloc&) { bad = true; return; }
+        const bool ok = parallel_chunks(n_parts, [&](int p) {
+            hist[(size_t)p].assign((size_t)c->V, 0);
             auto& h = hist[(size_t)p];
             const int32_t V = c->V;
             for (int64_t t = per * p; t < std::min(c->T_all, per * (p + 1)); ++t) {
@@ -817,7 +832,7 @@ int find_wide_rows(mlda_ctx* c, const int32_t* word_ids) {
                 if (w >= 0 && w < V) h[(size_t)w] += 1;      // (ids out of range are reported later)
             }
         });
-        if (bad) return fail(MLDA_ENOMEM, "out of host memory");
+        if (!ok) return fail(MLDA_ENOMEM, "out of host memory");
         c->wide_row.assign((size_t)c->V, -1);
         c->n_wide = 0;
         for (int32_t v = 0; v < c->V; ++v) {
@@ -1031,10 +1046,11 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
             e = hipMemcpyAsync(c->slot_base[0], h.arena, h.L.static_bytes, hipMemcpyHostToDevice, c->stream);
         if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
         if (rc == MLDA_OK) { derive_chunk_arrays(c); rc = finish_create(c, base, ML); }
-        if (rc == MLDA_OK) {
-            e = hipStreamSynchronize(c->stream);
-            if (e != hipSuccess) rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
-        }
+        // the upload reads the host arena until the stream has drained: wait for it before the
+        // arena goes, whether or not everything before went well
+        e = hipStreamSynchronize(c->stream);
+        if (rc == MLDA_OK && e != hipSuccess)
+            rc = fail(MLDA_EHIP, std::string("uploading the corpus: ") + hipGetErrorString(e));
         h.release();        // the corpus now lives on the device
     }
     if (rc != MLDA_OK) { destroy(c); return rc; }
@@ -1130,6 +1146,8 @@ int mlda_init_random(mlda_ctx* c) {
     c->iter = 0;
     c->has_state = true;
     c->ll_fresh = false;
+    c->last_step_iters = 0;     // the rows of mlda_get_timing / mlda_get_sampler_bytes belong to a step
+    c->timed_iters = 0;
     return MLDA_OK;
 }
 
@@ -1159,6 +1177,8 @@ int mlda_set_assignments(mlda_ctx* c, const uint16_t* z, int32_t iter) {
     c->iter = iter;
     c->has_state = true;
     c->ll_fresh = false;
+    c->last_step_iters = 0;
+    c->timed_iters = 0;
     return MLDA_OK;
 }
 

@@ -84,3 +84,10 @@ def test_null_context_calls_fail_cleanly(lib):
     assert lib.mlda_philox_uniform(1, 1, 0, -5, None, None) == -1
     assert lib.mlda_philox_uniform(1, 1, 0, 0, None, None) == 0
     lib.mlda_destroy(None)
+
+
+def test_binding_checks_array_lengths_before_the_library_reads_them(lib):
+    words = np.array([0, 1, 2, 1, 0], dtype=np.int32)
+    for bad_ptr in ([0, 2, 6], [0, 2, 4], [1, 2, 5], []):
+        with pytest.raises(ValueError):
+            mlda.Mlda(np.array(bad_ptr, dtype=np.int64), words, 3, 4, 0.5, 0.01, 1)

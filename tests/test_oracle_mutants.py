@@ -53,7 +53,7 @@ MUTANTS = [
 
 
 def run_pins(lib_path):
-    env = dict(os.environ, LDA_ORACLE_LIB=lib_path, OMP_NUM_THREADS="2")
+    env = dict(os.environ, LDA_ORACLE_LIB=lib_path, LDA_ORACLE_MUTATION_TEST="1", OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_TESTS],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     return r.returncode, r.stdout[-400:]
