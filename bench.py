@@ -24,9 +24,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
 # HBM bytes per sampling launch from rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by a
 # copy kernel of known size); filled in from the summaries under profiles/ per workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/sample_kernel_C4.md: FETCH_SIZE 1.17496e8 KiB x 2.000 + WRITE_SIZE 2.4738e6 KiB x 1.000
-    ("C4", "init"): (1.17496e8 * 2.000 + 2.4738e6 * 1.000) * 1024.0,
+# (FETCH_SIZE KiB, WRITE_SIZE KiB) per launch; FETCH_SIZE under-reports a plain copy by 2.000 on
+# this chip, WRITE_SIZE by 1.000 (same summaries).
+FETCH_SCALE, WRITE_SCALE = 2.000, 1.000
+MEASURED_TRAFFIC_KIB = {
+    ("C4", "init"): (1.17496e8, 2.4738e6, "profiles/sample_kernel_C4.md"),
+    ("C3", "init"): (2.0689e7, 3.70e5, "profiles/sample_kernel_C3_C5.md"),
+    ("C5", "init"): (2.8363e7, 1.347e6, "profiles/sample_kernel_C3_C5.md"),
 }
 
 
@@ -53,31 +57,53 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(cfg, seed, target_tokens):
-    """The oracle's full pass, as it stands, on a bounded sample of the same workload:
-    the first documents of the same configuration as a corpus of their own."""
-    import numpy as np
-    import corpus_synth
+def oracle_pass_rate(sample, cfg, seed, z, it, threads):
+    """tokens/s of one whole oracle iteration (resample, recount, theta CSR, log-likelihood)
+    from the state z."""
     import oracle
-    scale = min(1.0, target_tokens / (cfg.D * cfg.mean_len))
-    sample = corpus_synth.generate(cfg, scale=scale)
-    z = oracle.init_topics(sample.T, cfg.K, seed)
     n_wk, n_k = oracle.count_word_topic(sample.word_ids, z, cfg.V, cfg.K)
-    threads = oracle.max_threads()
     t0 = time.perf_counter()
     z1 = oracle.iteration(sample.doc_ptr, sample.word_ids, z, cfg.V, cfg.K, cfg.alpha, cfg.beta,
-                          seed, 1, n_wk, n_k, threads=threads)
+                          seed, it, n_wk, n_k, threads=threads)
     n_wk, n_k = oracle.count_word_topic(sample.word_ids, z1, cfg.V, cfg.K)
     oracle.doc_topic_csr(sample.doc_ptr, z1, cfg.K)
     oracle.loglik(sample.doc_ptr, z1, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
-    dt = time.perf_counter() - t0
+    return sample.T / (time.perf_counter() - t0)
+
+
+def cpu_baseline(cfg, seed, target_tokens):
+    """The oracle's full pass, as it stands, on a bounded sample of the same workload (the
+    first documents of the same configuration as a corpus of their own), from two states:
+    random topics (dense theta rows, the first iteration) and the topics the corpus was
+    generated with (sparse rows, a late iteration); the figure is the mean of the two.
+    Timed on all host threads and, on a sixteenth of the sample, on one thread."""
+    import corpus_synth
+    import oracle
+    threads = oracle.max_threads()
+    t_start = time.perf_counter()
+    scale = min(1.0, target_tokens / (cfg.D * cfg.mean_len))
+    sample = corpus_synth.generate(cfg, scale=scale)
+    small = corpus_synth.generate(cfg, scale=scale / 16.0)
+    rates = {}
+    for label, corpus, n_threads in (("all", sample, threads), ("one", small, 1)):
+        z_random = oracle.init_topics(corpus.T, cfg.K, seed)
+        rates[label] = [oracle_pass_rate(corpus, cfg, seed, z_random, 1, n_threads),
+                        oracle_pass_rate(corpus, cfg, seed, corpus.z_true, 1, n_threads)]
+    mean_all = sum(rates["all"]) / 2.0
+    mean_one = sum(rates["one"]) / 2.0
     return {
-        "value": sample.T / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": "one oracle iteration (resample + recount + log-likelihood) from the random "
-                  "initial state on the first %d documents (%d tokens) of the same configuration; "
-                  "sampling uses %d OpenMP threads, the recounts one" % (len(sample.doc_ptr) - 1,
-                                                                         sample.T, threads),
-        "seconds": dt,
+        "value": mean_all, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": "whole oracle iterations (resample + recount + theta CSR + log-likelihood) on the "
+                  "first %d documents (%d tokens) of the same configuration, mean of two start "
+                  "states (random topics %.4g tokens/s, generated topics %.4g tokens/s); sampling "
+                  "uses %d OpenMP threads, the recounts one"
+                  % (len(sample.doc_ptr) - 1, sample.T, rates["all"][0], rates["all"][1], threads),
+        "single_thread": {
+            "value": mean_one, "unit": "tokens/s", "cores": 1,
+            "sample": "the same on the first %d documents (%d tokens), one thread"
+                      % (len(small.doc_ptr) - 1, small.T),
+        },
+        "seconds": time.perf_counter() - t_start,
     }
 
 
@@ -176,7 +202,12 @@ def main():
     mean_ms = ms.mean(axis=0)
     sample_ms = float(mean_ms[0])
     achieved = float((algo_bytes / (ms[:, 0] * 1e-3)).mean()) / 1e9      # GB/s, per launch then mean
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, args.state))
+    measured = MEASURED_TRAFFIC_KIB.get((cfg.name, args.state))
+    traffic = traffic_source = hbm_gbs = None
+    if measured:
+        traffic = (measured[0] * FETCH_SCALE + measured[1] * WRITE_SCALE) * 1024.0
+        traffic_source = measured[2]
+        hbm_gbs = traffic / (sample_ms * 1e-3) / 1e9
     value = T * args.steps / elapsed
     log("per iteration: sample %.2f ms, phi %.2f ms, theta %.2f ms, loglik %.2f ms; wall %.2f ms"
         % (*mean_ms, elapsed / args.steps * 1e3))
@@ -221,17 +252,26 @@ def main():
             "traffic": traffic,
             "avg_launch_ms": sample_ms,
             "algorithmic_bytes_per_launch": float(algo_bytes.mean()),
+            # the two rates side by side: `useful` moves the bytes the method needs (one walk of
+            # its theta row per token, so rows that co-resident tiles share in cache count once
+            # per token), `hbm` the bytes the memory counters saw per launch in the committed
+            # profile of this command, over this run's launch time
+            "useful_gbs": achieved,
+            "useful_frac": achieved / HBM_PEAK_GBS,
+            "hbm_gbs": hbm_gbs,
+            "hbm_frac": hbm_gbs / HBM_PEAK_GBS if hbm_gbs else None,
+            "traffic_source": traffic_source,
         },
     }
     model.close()
     del model
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        target = args.cpu_sample_tokens or 1.0e11 / cfg.K      # about 10-30 s of oracle work
+        target = args.cpu_sample_tokens or 5.0e10 / cfg.K      # about 10-30 s of oracle work in all
         out["cpu_baseline"] = cpu_baseline(cfg, seed, target)
-        log("oracle: %.4g tokens/s on %d threads (%.1f s)" % (out["cpu_baseline"]["value"],
-                                                              out["cpu_baseline"]["cores"],
-                                                              out["cpu_baseline"]["seconds"]))
+        log("oracle: %.4g tokens/s on %d threads, %.4g on one (%.1f s)"
+            % (out["cpu_baseline"]["value"], out["cpu_baseline"]["cores"],
+               out["cpu_baseline"]["single_thread"]["value"], out["cpu_baseline"]["seconds"]))
     print(json.dumps(out), flush=True)
 
 
