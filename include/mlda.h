@@ -106,6 +106,28 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
                          int32_t n_chunks, void* dev_workspace, size_t workspace_bytes,
                          void* hip_stream);
 
+/*
+ * mlda_create for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc) and so have no workspace to hand over:
+ * the context works in a static device array of MLDA_STATIC_WORKSPACE_BYTES that belongs to
+ * the library (each GPU the library is used on holds its own copy until the process ends).
+ * The call, and every later call on the context, allocates no device memory.  Everything else
+ * is as for mlda_create, with the same kernels and bit-identical results.
+ *   - A corpus whose mlda_workspace_bytes exceeds MLDA_STATIC_WORKSPACE_BYTES is refused with
+ *     MLDA_ENOMEM (the message names both sizes): use mlda_create for it.
+ *   - The array is shared by all such contexts of the process on one GPU, so only one of them
+ *     may be alive per GPU at a time: a second call on the same device before mlda_destroy of
+ *     the first returns MLDA_EINVAL (two contexts working in the one array would race).  The
+ *     device that is current at the call is the one whose array is used; hip_stream must be
+ *     a stream of that device.
+ *   - The array keeps what the previous context left there; the library initialises
+ *     every part it reads, as it does for a caller's uninitialised workspace.
+ */
+#define MLDA_STATIC_WORKSPACE_BYTES (64u << 20)
+int mlda_create_static(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
+                       int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                       void* hip_stream);
+
 /* Random initial topics (Section 2.1), z[t] = floor(u(seed, 0, t) K); rebuilds all
  * counts; the iteration counter becomes 0. */
 int mlda_init_random(mlda_ctx* ctx);

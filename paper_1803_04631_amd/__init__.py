@@ -15,6 +15,7 @@ import numpy as np
 from ._build import LIB_PATH, build  # noqa: F401  (re-exported)
 
 STEP_LOGLIK = 1
+STATIC_WORKSPACE_BYTES = 64 << 20     # MLDA_STATIC_WORKSPACE_BYTES of include/mlda.h
 
 _lib = None
 
@@ -42,6 +43,7 @@ def load_library() -> ctypes.CDLL:
         "mlda_create": [p, p, p, i64, i32, i32, dbl, dbl, u64, p, sz, p],
         "mlda_workspace_bytes_streamed": [p, i64, i32, i32, i32, p],
         "mlda_create_streamed": [p, p, p, i64, i32, i32, dbl, dbl, u64, i32, p, sz, p],
+        "mlda_create_static": [p, p, p, i64, i32, i32, dbl, dbl, u64, p],
         "mlda_init_random": [p],
         "mlda_set_assignments": [p, p, i32],
         "mlda_step": [p, i32, u32],
@@ -71,7 +73,7 @@ def load_library() -> ctypes.CDLL:
 
 
 EXPORTED = ["mlda_workspace_bytes", "mlda_create", "mlda_workspace_bytes_streamed",
-            "mlda_create_streamed", "mlda_init_random", "mlda_set_assignments",
+            "mlda_create_streamed", "mlda_create_static", "mlda_init_random", "mlda_set_assignments",
             "mlda_step", "mlda_iteration", "mlda_get_assignments", "mlda_get_word_topic",
             "mlda_get_topic_totals", "mlda_get_doc_topic_nnz", "mlda_get_doc_topic_csr",
             "mlda_get_loglik", "mlda_get_timing", "mlda_get_sampler_bytes", "mlda_destroy",
@@ -102,10 +104,11 @@ def philox_uniform(seed: int, it: int, token0: int, n: int):
 class Mlda:
     """One corpus on the GPU: resident (Algorithm 1, WorkSchedule1 with a single chunk), or with
     chunks > 1 cut by document into that many chunks that are streamed through the GPU every
-    iteration (WorkSchedule2)."""
+    iteration (WorkSchedule2).  static_workspace: no device memory is allocated, the context
+    works in the library's own static array (mlda_create_static; small corpora only)."""
 
     def __init__(self, doc_ptr, word_ids, V: int, K: int, alpha: float, beta: float, seed: int,
-                 device: str = "cuda:0", chunks: int = 1):
+                 device: str = "cuda:0", chunks: int = 1, static_workspace: bool = False):
         import torch
         self.doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
         word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
@@ -123,7 +126,15 @@ class Mlda:
         with torch.cuda.device(self.device):
             self.stream = torch.cuda.current_stream(self.device)
             ctx = ctypes.c_void_p()
-            if self.chunks == 1:
+            if static_workspace:
+                if self.chunks != 1:
+                    raise ValueError("the static workspace holds a resident corpus only")
+                self.workspace = None
+                _check(self._lib.mlda_create_static(ctypes.addressof(ctx), self.doc_ptr.ctypes.data,
+                                                    word_ids.ctypes.data, self.D, self.V, self.K,
+                                                    self.alpha, self.beta, self.seed,
+                                                    self.stream.cuda_stream))
+            elif self.chunks == 1:
                 need = workspace_bytes(self.D, self.T, self.V, self.K)
                 self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
                 _check(self._lib.mlda_create(ctypes.addressof(ctx), self.doc_ptr.ctypes.data,

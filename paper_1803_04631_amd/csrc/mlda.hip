@@ -17,6 +17,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -451,9 +452,48 @@ struct mlda_ctx {
     mlda::Tile* tiles = nullptr;         // sampling tiles
     mlda::Tile* segs = nullptr;          // phi rebuild segments
     int32_t n_tiles = 0, n_segs = 0, n_split = 0, n_wide_tiles = 0;
+
+    int static_device = -1;              // >= 0: the workspace is that device's static array
 };
 
+// Workspace of contexts made by mlda_create_static: device memory that belongs to the library's
+// code object, one copy per GPU, held until the process ends.  In host code the array's name
+// is only a handle for hipGetSymbolAddress; kernels and copies take the address it returns.
+static __device__ __align__(256) unsigned char scratch[MLDA_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};      // address of `scratch` on each device, once known
+const mlda_ctx* g_scratch_user[kMaxDevices] = {};    // the live context that works in it, if any
+
+// The current device's copy of `scratch`, claimed for `user`.  One context per device at a time.
+int claim_scratch(const mlda_ctx* user, int* device, unsigned char** ptr) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MLDA_ENOTSUP, "device index beyond the library's table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_user[dev])
+        return fail(MLDA_EINVAL, "this device's static workspace is in use by another context: "
+                                 "destroy that context first");
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p) % kAlign != 0) return fail(MLDA_EHIP, "static workspace has no usable address");
+        g_scratch_ptr[dev] = (unsigned char*)p;
+    }
+    g_scratch_user[dev] = user;
+    *device = dev;
+    *ptr = g_scratch_ptr[dev];
+    return MLDA_OK;
+}
+
+void release_scratch(const mlda_ctx* user) {
+    if (user->static_device < 0) return;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_user[user->static_device] == user) g_scratch_user[user->static_device] = nullptr;
+}
 
 int launch_check(const char* what) {
     hipError_t e = hipGetLastError();
@@ -752,6 +792,10 @@ int check_workspace(void* dev_workspace, size_t have, size_t need) {
     if (have < need)
         return fail(MLDA_ENOMEM, "workspace has " + std::to_string(have) + " bytes, need " +
                                      std::to_string(need));
+    return MLDA_OK;
+}
+
+int check_device_pointer(void* dev_workspace) {
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, dev_workspace);
     if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
@@ -888,6 +932,7 @@ void destroy(mlda_ctx* c) {
         if (c->slot_free[s]) (void)hipEventDestroy(c->slot_free[s]);
     }
     if (c->z_host) (void)hipHostFree(c->z_host);
+    release_scratch(c);
     delete c;
 }
 
@@ -1010,18 +1055,36 @@ int mlda_workspace_bytes_streamed(const int64_t* doc_ptr, int64_t D, int32_t V, 
     return MLDA_OK;
 }
 
-int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
-                int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
-                void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+// mlda_create and mlda_create_static: the corpus resident in one workspace.  With
+// `in_static` the workspace is the current device's static array, claimed here.
+static int create_resident(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
+                           int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                           void* dev_workspace, size_t workspace_bytes, void* hip_stream, bool in_static) {
     if (!out) return fail(MLDA_EINVAL, "out is null");
     *out = nullptr;
     RC_TRY(check_corpus(doc_ptr, word_ids, true, D, V, K, alpha, beta));
     const int64_t T = doc_ptr[D];
     size_t need_bound = 0;
     if (mlda_workspace_bytes(D, T, V, K, &need_bound) != MLDA_OK) return MLDA_EINVAL;
-    RC_TRY(check_workspace(dev_workspace, workspace_bytes, need_bound));
+    if (in_static) {
+        if (need_bound > (size_t)MLDA_STATIC_WORKSPACE_BYTES)
+            return fail(MLDA_ENOMEM, "this corpus needs a workspace of " + std::to_string(need_bound) +
+                                         " bytes, the static one holds " +
+                                         std::to_string((size_t)MLDA_STATIC_WORKSPACE_BYTES) +
+                                         ": use mlda_create with a workspace of the caller's");
+    } else {
+        RC_TRY(check_workspace(dev_workspace, workspace_bytes, need_bound));
+        RC_TRY(check_device_pointer(dev_workspace));
+    }
     mlda_ctx* c = new (std::nothrow) mlda_ctx();
     if (!c) return fail(MLDA_ENOMEM, "out of host memory");
+    if (in_static) {
+        unsigned char* ptr = nullptr;
+        const int rc_claim = claim_scratch(c, &c->static_device, &ptr);
+        if (rc_claim != MLDA_OK) { delete c; return rc_claim; }
+        dev_workspace = ptr;
+        workspace_bytes = (size_t)MLDA_STATIC_WORKSPACE_BYTES;
+    }
     c->D_all = D; c->T_all = T; c->V = V; c->K = K;
     c->alpha = alpha; c->beta = beta; c->seed = seed;
     c->stream = (hipStream_t)hip_stream;
@@ -1058,6 +1121,18 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
     return MLDA_OK;
 }
 
+int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
+                int32_t V, int32_t K, double alpha, double beta, uint64_t seed,
+                void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+    return create_resident(out, doc_ptr, word_ids, D, V, K, alpha, beta, seed, dev_workspace,
+                           workspace_bytes, hip_stream, false);
+}
+
+int mlda_create_static(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
+                       int32_t V, int32_t K, double alpha, double beta, uint64_t seed, void* hip_stream) {
+    return create_resident(out, doc_ptr, word_ids, D, V, K, alpha, beta, seed, nullptr, 0, hip_stream, true);
+}
+
 int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids, int64_t D,
                          int32_t V, int32_t K, double alpha, double beta, uint64_t seed, int32_t n_chunks,
                          void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
@@ -1068,6 +1143,7 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     const int64_t T = doc_ptr[D];
     RC_TRY(check_workspace(dev_workspace, workspace_bytes,
                            streamed_workspace_bound(doc_ptr, D, V, K, n_chunks)));
+    RC_TRY(check_device_pointer(dev_workspace));
     mlda_ctx* c = new (std::nothrow) mlda_ctx();
     if (!c) return fail(MLDA_ENOMEM, "out of host memory");
     c->D_all = D; c->T_all = T; c->V = V; c->K = K;
