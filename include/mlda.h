@@ -180,10 +180,12 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
 /*
  * Algorithmic bytes each sampling launch of the most recent mlda_step had to move
  * (Section 3.1's accounting, with p* shared per word tile): per token 16 bytes (slot of
- * its theta row, token id, old and new topic, row length) plus 4 bytes per entry of its theta row
- * (6 if some document has 2^14 or more tokens: counts then need their own 32-bit words),
- * plus the word's row of phi per tile: 2 K bytes (Section 6.1.3: short integers), 4 K for a word
- * with 2^16 tokens or more, whose counts the library keeps as int32.  bytes: host, capacity_iters doubles, out; rows as in
+ * its theta row, token id, old and new topic, row length) plus the entries of its theta row
+ * (Section 6.1.3's compression taken further: 2 bytes per entry when K < 1024, ten bits of
+ * topic and four of count, else 4 bytes, sixteen bits of topic and fourteen of count; a count
+ * beyond its field takes several entries), plus the word's row of phi per tile: 2 K bytes
+ * (Section 6.1.3: short integers), 4 K for a word with 2^16 tokens or more, whose counts the
+ * library keeps as int32.  bytes: host, capacity_iters doubles, out; rows as in
  * mlda_get_timing.
  */
 int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);

@@ -166,16 +166,51 @@ __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const 
     return doc_map ? doc_map[r.begin + j] : r.begin + j;
 }
 
-// LDS bytes of the rebuild's dense row.  Rows with 4-byte entries hold counts below 2^14:
-// two 16-bit counters per dword plus one bit per topic that marks the non-zero bins.  Rows
-// with 6-byte entries keep one int32 counter per topic.
-__host__ __device__ inline size_t theta_hist_bytes(int32_t K, bool packed) {
-    const size_t counters = packed ? (size_t)((K + 1) / 2) * 4 : (size_t)K * 4;
-    const size_t marks = packed ? (size_t)((K + 31) / 32) * 4 : 0;
-    return ((counters + 15) & ~(size_t)15) + ((marks + 15) & ~(size_t)15);
+// LDS bytes of the rebuild's dense row: the counters (two 16-bit counters per dword, or one
+// 32-bit counter per topic when some document has 2^16 tokens or more), then one bit per topic
+// that marks the non-zero bins.
+__host__ __device__ inline size_t theta_counter_bytes(int32_t K, bool wide) {
+    const size_t counters = wide ? (size_t)K * 4 : (size_t)((K + 1) / 2) * 4;
+    return (counters + 15) & ~(size_t)15;
 }
-__host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool packed) {
-    return theta_hist_bytes(K, packed) + (size_t)kThetaLgTable * 8;
+__host__ __device__ inline size_t theta_hist_bytes(int32_t K, bool wide) {
+    const size_t marks = (size_t)((K + 31) / 32) * 4;
+    return theta_counter_bytes(K, wide) + ((marks + 15) & ~(size_t)15);
+}
+__host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool wide) {
+    return theta_hist_bytes(K, wide) + (size_t)kThetaLgTable * 8;
+}
+
+// Entries a count of c > 0 takes in a row whose entries hold at most kMax each.
+template <class Layout>
+__device__ __forceinline__ int entries_of(int c) {
+    return (c + Layout::kMaxCount - 1) / Layout::kMaxCount;
+}
+
+// The entries of topic k with count c > 0, written from ent[at] on; returns the next place.
+template <class Layout>
+__device__ __forceinline__ int write_entries(typename Layout::Entry* ent, int at, int k, int c) {
+    while (c > Layout::kMaxCount) {
+        ent[at++] = Layout::make(Layout::kMaxCount, k);
+        c -= Layout::kMaxCount;
+    }
+    ent[at++] = Layout::make(c, k);
+    return at;
+}
+
+// What closes a row: padding entries up to a whole unit (lanes 0 .. 6 of `hl`), the number of
+// entries at the head of the slot and a padding entry at the header's very end, so that the
+// entry "before the first" is never anybody's topic.
+template <class Layout>
+__device__ __forceinline__ void close_row(unsigned char* head, int n_entries, int K, int hl, bool real) {
+    typedef typename Layout::Entry Entry;
+    Entry* ent = reinterpret_cast<Entry*>(head + kRowHeader);
+    const int padded = (n_entries + Layout::kUnitEntries - 1) / Layout::kUnitEntries * Layout::kUnitEntries;
+    if (real && hl < padded - n_entries) ent[n_entries + hl] = Layout::make(0, K);
+    if (real && hl == 0) {
+        *reinterpret_cast<uint32_t*>(head) = (uint32_t)n_entries;
+        ent[-1] = Layout::make(0, K);
+    }
 }
 
 // Update theta (Section 6.2): document by document, (1) a dense K-long histogram of the
@@ -186,13 +221,13 @@ __host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool packed) {
 // together gather from neighbouring lines of z.  The walk is a chain of dependent loads
 // (record -> map -> z), so it is software-pipelined: while the current document is counted,
 // the topics of the wave's next document, the map entries of the one after and the record
-// after that are already on their way.  Rows are written in the layout the sampler reads (SplitRows or
-// PackedRows, see kernels_sample.hpp); padding entries hold count 0 and topic K.
-// With PackedRows the compaction visits only the 32-topic groups that hold a non-zero bin
-// (one mark bit per topic), so its cost follows the row's length rather than K.
-// While the counts pass through registers the kernel also adds up the theta entries' term of
-// the log-likelihood, sum_{d,k} lgG(n_dk + alpha) - lgG(alpha), one partial per workgroup.
-template <bool kPacked>
+// after that are already on their way.  Rows are written in the layout the sampler reads
+// (PackedRows or TinyRows, see kernels_sample.hpp).  The compaction visits only the 32-topic
+// groups that hold a non-zero bin (one mark bit per topic), so its cost follows the row's
+// length rather than K.  While the counts pass through registers the kernel also adds up the
+// theta entries' term of the log-likelihood, sum_{d,k} lgG(n_dk + alpha) - lgG(alpha), one
+// partial per workgroup.
+template <class Layout, bool kWide>
 __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                                                            const int32_t* doc_map,
                                                            const uint16_t* z, uint2* row_rec,
@@ -201,20 +236,20 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                                                            const double* lg_table,
                                                            unsigned long long* row_entries,
                                                            double* ll_partial) {
+    typedef typename Layout::Entry Entry;
     extern __shared__ __align__(16) unsigned char lds[];
-    // kPacked: `hist` holds (K+1)/2 dwords of paired 16-bit counters, `marks` one bit per topic
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
-    const int n_counters = kPacked ? (K + 1) / 2 : K;
-    const int n_marks = kPacked ? (K + 31) / 32 : 0;
-    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (((size_t)n_counters * 4 + 15) & ~(size_t)15));
-    double* table = reinterpret_cast<double*>(lds + theta_hist_bytes(K, kPacked));
+    const int n_counters = kWide ? K : (K + 1) / 2;
+    const int n_marks = (K + 31) / 32;
+    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + theta_counter_bytes(K, kWide));
+    double* table = reinterpret_cast<double*>(lds + theta_hist_bytes(K, kWide));
     const int lane = (int)threadIdx.x;
     const double lg_alpha = lg_table[kLgTable];
     for (int k = lane; k < n_counters; k += kWave) hist[k] = 0u;
     for (int k = lane; k < n_marks; k += kWave) marks[k] = 0u;
     for (int c = lane; c < kThetaLgTable; c += kWave) table[c] = lg_table[c];
     __syncthreads();
-    unsigned long long visited = 0;      // sum of N_d * nnz_d over this wave's documents
+    unsigned long long visited = 0;      // sum of N_d * (entries of row d) over this wave's documents
     double ll = 0.0;
     // lgG(c + alpha) - lgG(alpha) added to `ll`; the rare large counts go through a branch the
     // whole wave takes or skips, so that the common case never pays for the logarithm
@@ -225,14 +260,21 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                 ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
         }
     };
-    // one more token of topic k in the dense row; returns 1 if it is the topic's first
-    auto count_topic = [&](int k) -> int {
-        if (kPacked) {
-            atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
-            atomicOr(&marks[k >> 5], 1u << (k & 31));
-            return 0;                     // the row's length comes from the marks instead
-        }
-        return atomicAdd(&hist[k], 1u) == 0u ? 1 : 0;
+    // one more token of topic k; true if the topic's count has outgrown one entry
+    auto count_topic = [&](int k) -> bool {
+        atomicOr(&marks[k >> 5], 1u << (k & 31));
+        if (kWide) return (int)atomicAdd(&hist[k], 1u) >= Layout::kMaxCount;
+        const uint32_t before = atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
+        return (int)((before >> ((k & 1) << 4)) & 0xffffu) >= Layout::kMaxCount;
+    };
+    // the same for a document too short for that (the atomics then return nothing)
+    auto count_topic_short = [&](int k) {
+        atomicOr(&marks[k >> 5], 1u << (k & 31));
+        if (kWide) atomicAdd(&hist[k], 1u);
+        else atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
+    };
+    auto count_of = [&](int k) -> int {    // (narrow counters: the pair's other half stays)
+        return kWide ? (int)hist[k] : (int)((hist[k >> 1] >> ((k & 1) << 4)) & 0xffffu);
     };
     const int64_t step = gridDim.x;
     const DocRec none = {0, 0, 0u, 0};
@@ -265,30 +307,54 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         const int q1 = doc_token_position(doc_map, after, lane + kWave);
         const DocRec later = i + 3 * step < D ? docs[i + 3 * step] : none;
 
-        int fresh = 0;                    // first token of a topic
-        if (k0 >= 0) fresh += count_topic(k0);
-        if (k1 >= 0) fresh += count_topic(k1);
-        for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
-            fresh += count_topic((int)z[doc_token_position(doc_map, cur, j)]);
+        bool outgrown = false;
+        if (cur.n > Layout::kMaxCount) {
+            if (k0 >= 0) outgrown |= count_topic(k0);
+            if (k1 >= 0) outgrown |= count_topic(k1);
+            for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
+                outgrown |= count_topic((int)z[doc_token_position(doc_map, cur, j)]);
+        } else {
+            if (k0 >= 0) count_topic_short(k0);
+            if (k1 >= 0) count_topic_short(k1);
+            for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
+                count_topic_short((int)z[doc_token_position(doc_map, cur, j)]);
+        }
         __syncthreads();
-        int nnz;
         unsigned char* head = slots + (size_t)cur.slot * 16u;
-        unsigned char* slot = head + kRowHeader;
-        if constexpr (kPacked) {
-            // uint32 entries count << 18 | topic << 2.  Each lane owns one word of marks
-            // (32 topics = 16 counter pairs) and writes its non-zero bins in ascending order
-            // behind those of the lanes below it.
-            uint32_t* ent = reinterpret_cast<uint32_t*>(slot);
-            int filled = 0;
-            for (int base = 0; base < n_marks; base += kWave) {
-                const int wi = base + lane;
-                const uint32_t w = wi < n_marks ? marks[wi] : 0u;
-                if (__ballot(w != 0u) == 0) continue;
-                const int mine = __popc(w);
-                const int upto = wave_inclusive_sum(mine);
-                int at = filled + upto - mine;
-                filled += read_lane(upto, kWave - 1);
-                if (w != 0u) marks[wi] = 0u;
+        Entry* ent = reinterpret_cast<Entry*>(head + kRowHeader);
+        // some count of the document takes several entries
+        const bool may_split = __ballot(outgrown) != 0;
+        // Each lane owns one word of marks (32 topics) per round and writes its non-zero bins
+        // in ascending order behind those of the lanes below it.
+        int filled = 0, distinct = 0;
+        for (int base = 0; base < n_marks; base += kWave) {
+            const int wi = base + lane;
+            uint32_t w = wi < n_marks ? marks[wi] : 0u;
+            if (__ballot(w != 0u) == 0) continue;
+            int mine = __popc(w);
+            distinct += mine;
+            if (may_split) {           // the lane's entries, counted one bin at a time
+                mine = 0;
+                for (uint32_t rest = w; rest != 0u; rest &= rest - 1u)
+                    mine += entries_of<Layout>(count_of(wi * 32 + __ffs((int)rest) - 1));
+            }
+            const int upto = wave_inclusive_sum(mine);
+            int at = filled + upto - mine;
+            filled += read_lane(upto, kWave - 1);
+            if (w != 0u) marks[wi] = 0u;
+            if (kWide) {
+                while (__ballot(w != 0u) != 0) {
+                    int c = 0;
+                    if (w != 0u) {
+                        const int k = wi * 32 + __ffs((int)w) - 1;
+                        w &= w - 1u;
+                        c = (int)hist[k];
+                        hist[k] = 0u;
+                        at = write_entries<Layout>(ent, at, k, c);
+                    }
+                    add_ll(c);
+                }
+            } else {
                 uint32_t pairs = (w | (w >> 1)) & 0x55555555u;
                 while (__ballot(pairs != 0u) != 0) {
                     int lo = 0, hi = 0;
@@ -299,44 +365,18 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                         hist[k >> 1] = 0u;
                         lo = (int)(both & 0xffffu);
                         hi = (int)(both >> 16);
-                        if (lo != 0) ent[at++] = ((uint32_t)lo << 18) | ((uint32_t)k << 2);
-                        if (hi != 0) ent[at++] = ((uint32_t)hi << 18) | ((uint32_t)(k + 1) << 2);
+                        if (lo != 0) at = write_entries<Layout>(ent, at, k, lo);
+                        if (hi != 0) at = write_entries<Layout>(ent, at, k + 1, hi);
                     }
                     add_ll(lo);
                     add_ll(hi);
                 }
             }
-            nnz = filled;
-            const int nnz_pad = (nnz + 3) & ~3;
-            if (lane < nnz_pad - nnz) ent[nnz + lane] = (uint32_t)K << 2;
-        } else {
-            // int32 counts[round4(nnz)], then uint16 topics
-            nnz = wave_sum(fresh);
-            const int nnz_pad = (nnz + 3) & ~3;
-            int32_t* cnt = reinterpret_cast<int32_t*>(slot);
-            uint16_t* top = reinterpret_cast<uint16_t*>(cnt + nnz_pad);
-            int filled = 0;
-            for (int base = 0; base < K; base += kWave) {
-                const int k = base + lane;
-                const int c = (k < K) ? (int)hist[k] : 0;
-                const uint64_t m = __ballot(c > 0);
-                if (m == 0) continue;
-                if (c > 0) {
-                    const int at = filled + __popcll((unsigned long long)(m & lanes_below()));
-                    cnt[at] = c;
-                    top[at] = (uint16_t)k;
-                    hist[k] = 0u;
-                }
-                add_ll(c);
-                filled += __popcll((unsigned long long)m);
-            }
-            if (lane < nnz_pad - nnz) { cnt[nnz + lane] = 0; top[nnz + lane] = (uint16_t)K; }
         }
-        if (lane == 0) {                    // the row's length: in its slot for the sampler,
-            *reinterpret_cast<uint32_t*>(head) = (uint32_t)nnz;
-            row_rec[cur.doc].y = (uint32_t)nnz;      // and by document for the getters
-        }
-        visited += (unsigned long long)cur.n * (unsigned long long)nnz;
+        close_row<Layout>(head, filled, K, lane, true);
+        const int nnz = may_split ? wave_sum(distinct) : filled;
+        if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;      // distinct topics, for the getters
+        visited += (unsigned long long)cur.n * (unsigned long long)filled;
         __syncthreads();
         cur = nxt; nxt = after; after = later; k0 = n0; k1 = n1; p0 = q0; p1 = q1;
     }
@@ -345,14 +385,15 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     block_partial_store(ll, ll_partial);
 }
 
-// The same for rows with 4-byte entries and K <= 1024, two documents per wave: the mark bits
-// of a document then fit one word per lane of a half-wave (32 lanes x 32 topics), so lanes
-// 0..31 rebuild one document and lanes 32..63 the next one with the same instructions, which
-// halves the instructions per document.  Documents 2 p and 2 p + 1 (neighbours in the working
-// order, so of similar length) make pair p; the topics of the first 128 tokens of each document
-// of the next pair are on their way while the current pair is counted.
+// The same for K <= 1024 and documents of fewer than 2^16 tokens, two documents per wave: the
+// mark bits of a document then fit one word per lane of a half-wave (32 lanes x 32 topics), so
+// lanes 0..31 rebuild one document and lanes 32..63 the next one with the same instructions,
+// which halves the instructions per document.  Documents 2 p and 2 p + 1 (neighbours in the
+// working order, so of similar length) make pair p; the topics of the first 128 tokens of each
+// document of the next pair are on their way while the current pair is counted.
 constexpr int kPairMaxK = 1024;
 
+template <class Layout>
 __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* docs,
                                                                 const int32_t* doc_map,
                                                                 const uint16_t* z, uint2* row_rec,
@@ -361,21 +402,21 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
                                                                 const double* lg_table,
                                                                 unsigned long long* row_entries,
                                                                 double* ll_partial) {
+    typedef typename Layout::Entry Entry;
     extern __shared__ __align__(16) unsigned char lds[];
     const int lane = (int)threadIdx.x, half = lane >> 5, hl = lane & 31;
     const int n_counters = (K + 1) / 2, n_marks = (K + 31) / 32;
-    const size_t one = theta_hist_bytes(K, true);
+    const size_t one = theta_hist_bytes(K, false);
     // per half: paired 16-bit counters, then one mark bit per topic
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds + (size_t)half * one);
-    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (size_t)half * one +
-                                                  (((size_t)n_counters * 4 + 15) & ~(size_t)15));
+    uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (size_t)half * one + theta_counter_bytes(K, false));
     double* table = reinterpret_cast<double*>(lds + 2 * one);
     const double lg_alpha = lg_table[kLgTable];
     for (int k = hl; k < n_counters; k += 32) hist[k] = 0u;
     for (int k = hl; k < n_marks; k += 32) marks[k] = 0u;
     for (int c = lane; c < kThetaLgTable; c += kWave) table[c] = lg_table[c];
     __syncthreads();
-    unsigned long long visited = 0;      // sum of N_d * nnz_d over this half's documents
+    unsigned long long visited = 0;      // sum of N_d * (entries of row d) over this half's documents
     double ll = 0.0;
     auto add_ll = [&](int c) {
         if (c > 0 && c < kThetaLgTable) ll += table[c];
@@ -384,9 +425,11 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
                 ll += c < kLgTable ? lg_table[c] : lgamma_large((double)c + alpha) - lg_alpha;
         }
     };
-    auto count_topic = [&](int k) {
-        atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
+    // one more token of topic k; true if the topic's count has outgrown one entry
+    auto count_topic = [&](int k) -> bool {
+        const uint32_t before = atomicAdd(&hist[k >> 1], 1u << ((k & 1) << 4));
         atomicOr(&marks[k >> 5], 1u << (k & 31));
+        return (int)((before >> ((k & 1) << 4)) & 0xffffu) >= Layout::kMaxCount;
     };
     auto topic_at = [&](const DocRec& r, int j) {       // topic of the document's token j, -1 past its end
         const int p = doc_token_position(doc_map, r, j);
@@ -407,26 +450,44 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
         const int n0 = topic_at(nxt, hl), n1 = topic_at(nxt, hl + 32), n2 = topic_at(nxt, hl + 64),
                   n3 = topic_at(nxt, hl + 96);
         const DocRec after = record(i + 2 * step);
-        if (k0 >= 0) count_topic(k0);
-        if (k1 >= 0) count_topic(k1);
-        if (k2 >= 0) count_topic(k2);
-        if (k3 >= 0) count_topic(k3);
-        for (int j = 128 + hl; j < cur.n; j += 32) count_topic(topic_at(cur, j));
+        bool outgrown = false;
+        if (k0 >= 0) outgrown |= count_topic(k0);
+        if (k1 >= 0) outgrown |= count_topic(k1);
+        if (k2 >= 0) outgrown |= count_topic(k2);
+        if (k3 >= 0) outgrown |= count_topic(k3);
+        for (int j = 128 + hl; j < cur.n; j += 32) outgrown |= count_topic(topic_at(cur, j));
         __syncthreads();
         unsigned char* head = slots + (size_t)cur.slot * 16u;
-        uint32_t* ent = reinterpret_cast<uint32_t*>(head + kRowHeader);
+        Entry* ent = reinterpret_cast<Entry*>(head + kRowHeader);
         // lane hl of a half owns mark word hl: 32 topics = 16 counter pairs
         const uint32_t w = hl < n_marks ? marks[hl] : 0u;
-        const int mine = __popc(w);
+        const int distinct = __popc(w);
+        int mine = distinct;
+        if (__ballot(outgrown) != 0) {      // some count of the pair takes several entries
+            mine = 0;
+            for (uint32_t rest = w; rest != 0u; rest &= rest - 1u) {
+                const int k = hl * 32 + __ffs((int)rest) - 1;
+                mine += entries_of<Layout>((int)((hist[k >> 1] >> ((k & 1) << 4)) & 0xffffu));
+            }
+        }
         // prefix over the 32 lanes of each half: the wave-wide scan without its last step
-        int upto = mine;
-        upto += __builtin_amdgcn_update_dpp(0, upto, 0x111, 0xf, 0xf, false);
-        upto += __builtin_amdgcn_update_dpp(0, upto, 0x112, 0xf, 0xf, false);
-        upto += __builtin_amdgcn_update_dpp(0, upto, 0x114, 0xf, 0xf, false);
-        upto += __builtin_amdgcn_update_dpp(0, upto, 0x118, 0xf, 0xf, false);
-        upto += __builtin_amdgcn_update_dpp(0, upto, 0x142, 0xa, 0xf, false);
-        const int nnz_a = read_lane(upto, 31), nnz_b = read_lane(upto, 63);
-        const int nnz = half ? nnz_b : nnz_a;
+        auto half_inclusive_sum = [](int v) {
+            v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
+            v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);
+            v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);
+            v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);
+            v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+            return v;
+        };
+        const int upto = half_inclusive_sum(mine);
+        const int n_a = read_lane(upto, 31), n_b = read_lane(upto, 63);
+        const int n_entries = half ? n_b : n_a;
+        int nnz = n_entries;                              // distinct topics of the row
+        if (__ballot(mine != distinct) != 0) {
+            const int d_upto = half_inclusive_sum(distinct);
+            const int d_a = read_lane(d_upto, 31), d_b = read_lane(d_upto, 63);
+            nnz = half ? d_b : d_a;
+        }
         int at = upto - mine;
         if (w != 0u) marks[hl] = 0u;
         uint32_t pairs = (w | (w >> 1)) & 0x55555555u;
@@ -439,19 +500,17 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
                 hist[k >> 1] = 0u;
                 lo = (int)(both & 0xffffu);
                 hi = (int)(both >> 16);
-                if (lo != 0) ent[at++] = ((uint32_t)lo << 18) | ((uint32_t)k << 2);
-                if (hi != 0) ent[at++] = ((uint32_t)hi << 18) | ((uint32_t)(k + 1) << 2);
+                if (lo != 0) at = write_entries<Layout>(ent, at, k, lo);
+                if (hi != 0) at = write_entries<Layout>(ent, at, k + 1, hi);
             }
             add_ll(lo);
             add_ll(hi);
         }
         const bool real = 2 * i + half < D;              // the last pair may lack its second document
-        const int nnz_pad = (nnz + 3) & ~3;
-        if (real && hl < nnz_pad - nnz) ent[nnz + hl] = (uint32_t)K << 2;
+        close_row<Layout>(head, n_entries, K, hl, real);
         if (real && hl == 0) {
-            *reinterpret_cast<uint32_t*>(head) = (uint32_t)nnz;
-            row_rec[cur.doc].y = (uint32_t)nnz;
-            visited += (unsigned long long)cur.n * (unsigned long long)nnz;
+            row_rec[cur.doc].y = (uint32_t)nnz;          // distinct topics, for the getters
+            visited += (unsigned long long)cur.n * (unsigned long long)n_entries;
         }
         __syncthreads();
         cur = nxt; nxt = after; k0 = n0; k1 = n1; k2 = n2; k3 = n3;

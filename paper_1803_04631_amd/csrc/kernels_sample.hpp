@@ -14,16 +14,23 @@
 //     then the group's topics);
 //   - the walk over the token's sparse theta row (S and the p1 prefix sums, Eq. 6-7) is done
 //     by a GROUP of 4, 8, 16, 32 or 64 lanes per token, chosen per pass from the row lengths
-//     so that a lane owns at most twelve entries (16, 8, 4, 2 or 1 tokens per pass: the fixed
-//     cost of a pass is shared by as many tokens as their rows allow).  Groups narrower than
-//     a DPP row of 16 lanes are interleaved inside the row (4 or 2 tokens side by side), so
-//     that plain row shifts scan every group at once.  Every lane owns a contiguous run of
-//     entries, loaded four at a time, accumulates them in fp64 in registers, and a DPP scan
-//     over the group gives the prefix over lanes.  The lane whose range holds the draw finds
-//     "the smallest k whose prefix exceeds it" (Section 6.1.1) among its own entries.  Rows
-//     of more than 768 entries are walked twice by a whole wave.  Token parameters and
+//     so that a lane owns at most three 16-byte units of entries (16, 8, 4, 2 or 1 tokens per
+//     pass: the fixed cost of a pass is shared by as many tokens as their rows allow).  Groups
+//     narrower than a DPP row of 16 lanes are interleaved inside the row (4 or 2 tokens side by
+//     side), so that plain row shifts scan every group at once.  Every lane owns a contiguous
+//     run of entries, accumulates them in fp64 and keeps the sum at the end of each unit; a DPP
+//     scan over the group gives the prefix over lanes.  The lane whose range holds the draw
+//     names the unit that holds it and what is left of the draw there; "the smallest k whose
+//     prefix exceeds it" (Section 6.1.1) among that unit's few entries is found afterwards, one
+//     token per lane again, for all tokens of the batch at once.  Rows too long for three
+//     units per lane of a whole wave are walked twice by the wave.  Token parameters and
 //     results travel between the per-lane and per-group phases through small per-wave LDS
 //     records;
+//   - a theta row is a run of entries (topic, count) in ascending topic order, 2 bytes each
+//     when K < 1024 (10 bits of topic, 4 of count), else 4 bytes (16 bits of topic, 14 of
+//     count); a count too large for its field is written as several entries of the same
+//     topic, one after the other, which changes no sum.  Only the first entry of the token's
+//     own topic gives up the token itself;
 //   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
 //     loads of the next pass are issued before the current pass is worked on.
 #pragma once
@@ -57,8 +64,9 @@ struct SampleArgs {
     const uint16_t* z_cur;      // [T] word-major, frozen for the pass
     uint16_t* z_next;           // [T] word-major, written
     // theta rows: a slot (offset in 16-byte units) starts with a header of kRowHeader bytes
-    // whose first word is the row's length, then holds the entries in one of the two layouts
-    // below (SplitRows / PackedRows); padding entries hold count 0 and topic K
+    // whose first word is the row's number of entries and whose last bytes are a padding
+    // entry, then holds the entries in one of the two layouts below (PackedRows / TinyRows),
+    // filled up to a whole 16-byte unit with padding entries (count 0, topic K)
     const unsigned char* slots;
     PhiView phi;
     const int32_t* n_k;         // [K]
@@ -72,19 +80,23 @@ constexpr int kRowHeader = 16;  // bytes before a theta row's entries
 // Topics per fp64 prefix group of the dense bucket: 4 where LDS has room (workgroups of four
 // waves, K <= 2048), 16 for the large-K workgroups of twelve waves.
 __host__ __device__ constexpr int dense_group(int waves) { return waves == 4 ? 4 : 16; }
-constexpr int kKeptQuads = 3;   // quads (of four entries) a lane keeps in registers at most
+constexpr int kKeptUnits = 3;   // 16-byte units of entries a lane keeps in registers at most
 constexpr int kMinBatch = 8;    // tokens a wave takes at a time at least
 
 // Once a token's pass has read its record, the record takes the result back to the per-lane
-// phase: the new topic (or -1 for "dense bucket") in `off`, the dense draw position in `u`.
+// phase: `nnz` says what kind (below), `off` and `u` hold it.
 struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
     uint32_t off;               // slot offset of the token's theta row, 16-byte units
-    int32_t nnz;
+    int32_t nnz;                // entries of the row
     int32_t o;                  // current topic
     float w_o;                  // p*(o) with the token itself removed
     double u;
     double Qp;                  // alpha * sum_k p*'(k)
 };
+constexpr int kDrawInUnit = -1; // off = the 16-byte unit of the slot buffer that holds the draw,
+                                // u = what is left of the draw at the unit's start
+constexpr int kDrawDense = -2;  // the draw falls into the dense bucket p2; u = its position there
+constexpr int kDrawTopic = -3;  // off = the new topic itself
 
 // LDS bytes of sample_kernel<kWaves> for a given Kpad.
 __host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
@@ -175,81 +187,90 @@ __device__ __forceinline__ int group_last_lane(int lane) {
     return kLanes >= 16 ? (lane | (kLanes - 1)) : (lane | (16 - 16 / kLanes));
 }
 
-// Layout of a theta row inside its slot, 6 bytes per entry: int32 counts[round4(nnz)] then
-// uint16 topics[round4(nnz)].  Always usable.
-struct SplitRows {
-    static constexpr int kEntryBytes = 6;
+// Value of the sub-lane before this one inside the group (garbage for the group's first).
+template <int kLanes>
+__device__ __forceinline__ int group_previous_int(int v) {
+    if (kLanes == 16) return __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    if (kLanes == 8) return __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+    if (kLanes == 4) return __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
+    return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, true);                      // wave_shr:1
+}
+
+// ---------------------------------------------------------------- theta row layouts
+// A row's entries follow its 16-byte header in ascending topic order and are read in units of
+// 16 bytes.  A count beyond an entry's field is spread over several entries of the same topic.
+// key = 4 * topic = the byte offset of p*(topic) in LDS.
+
+// 4 bytes per entry: count << 18 | topic << 2.  Any K.
+struct PackedRows {
+    typedef uint32_t Entry;
+    static constexpr int kEntryBytes = 4, kUnitEntries = 4;
+    static constexpr int kMaxCount = (1 << 14) - 1;
+    static constexpr int kWavesPerSimd = 6;
+    static constexpr bool kOneEntryPerTopic = false;
+    static __host__ __device__ __forceinline__ Entry make(int count, int topic) {
+        return ((uint32_t)count << 18) | ((uint32_t)topic << 2);
+    }
+    static __host__ __device__ __forceinline__ int entry_topic(Entry e) { return (int)((e >> 2) & 0xffffu); }
+    static __host__ __device__ __forceinline__ int entry_count(Entry e) { return (int)(e >> 18); }
+    static __device__ __forceinline__ uint32_t word(const uint4& u, int j) {
+        return j == 0 ? u.x : j == 1 ? u.y : j == 2 ? u.z : u.w;
+    }
+    static __device__ __forceinline__ int key(const uint4& u, int j) { return (int)(word(u, j) & 0x3fffcu); }
+    static __device__ __forceinline__ int count(const uint4& u, int j) { return (int)(word(u, j) >> 18); }
+};
+
+// The same when no document has more tokens than an entry counts (the host checks): every topic
+// then has one entry, the row walk needs no look at the entry before, and with so few entries
+// per unit the search for the draw's entry is cheapest inside the pass itself.
+struct PackedRowsShort : PackedRows {
+    static constexpr bool kOneEntryPerTopic = true;
+};
+
+// 2 bytes per entry: count << 12 | topic << 2 (ten bits of topic, four of count).  K < 1024.
+struct TinyRows {
+    typedef uint16_t Entry;
+    static constexpr int kEntryBytes = 2, kUnitEntries = 8;
+    static constexpr int kMaxCount = 15;
+    static constexpr int kMaxK = 1023;          // topics 0 .. K, K being the padding entries'
     static constexpr int kWavesPerSimd = 5;
-    struct Raw {            // four consecutive entries as they come from memory
-        int4 c;             // counts
-        uint2 t;            // topics, two per dword
-    };
-    static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int nnz,
-                                               int e, bool on, int K) {
-        Raw q;
-        q.c = make_int4(0, 0, 0, 0);
-        q.t = make_uint2((uint32_t)K | ((uint32_t)K << 16), (uint32_t)K | ((uint32_t)K << 16));
-        if (on) {
-            const int32_t* cnt = reinterpret_cast<const int32_t*>(slots + (size_t)off * 16u + kRowHeader);
-            const uint16_t* top = reinterpret_cast<const uint16_t*>(cnt + ((nnz + 3) & ~3));
-            q.c = *reinterpret_cast<const int4*>(cnt + e);
-            q.t = *reinterpret_cast<const uint2*>(top + e);
-        }
-        return q;
+    static constexpr bool kOneEntryPerTopic = false;
+    static __host__ __device__ __forceinline__ Entry make(int count, int topic) {
+        return (Entry)(((uint32_t)count << 12) | ((uint32_t)topic << 2));
     }
-    static __device__ __forceinline__ int count(const Raw& q, int j) {
-        return j == 0 ? q.c.x : j == 1 ? q.c.y : j == 2 ? q.c.z : q.c.w;
+    static __host__ __device__ __forceinline__ int entry_topic(Entry e) { return (int)((e >> 2) & 0x3ffu); }
+    static __host__ __device__ __forceinline__ int entry_count(Entry e) { return (int)(e >> 12); }
+    static __device__ __forceinline__ uint32_t word(const uint4& u, int j) {
+        return (j >> 1) == 0 ? u.x : (j >> 1) == 1 ? u.y : (j >> 1) == 2 ? u.z : u.w;
     }
-    static __device__ __forceinline__ int key(const Raw& q, int j) {
-        return j == 0 ? (int)((q.t.x & 0xffffu) << 2) : j == 1 ? (int)((q.t.x >> 16) << 2)
-             : j == 2 ? (int)((q.t.y & 0xffffu) << 2) : (int)((q.t.y >> 16) << 2);
+    static __device__ __forceinline__ int key(const uint4& u, int j) {
+        const uint32_t d = word(u, j);
+        return (j & 1) ? (int)__builtin_amdgcn_ubfe(d, 16, 12) : (int)(d & 0xffcu);
     }
-    // what the search remembers of entry i of a lane's quads, and the topic it stands for
-    static __device__ __forceinline__ uint32_t handle(const Raw*, int i) { return (uint32_t)i; }
-    template <int kQuads>
-    static __device__ __forceinline__ int topic_of(const Raw* raw, uint32_t h) {
-        uint32_t pair = raw[0].t.x;
-#pragma unroll
-        for (int p = 1; p < 2 * kQuads; ++p)
-            if ((h >> 1) == (uint32_t)p) pair = (p & 1) ? raw[p / 2].t.y : raw[p / 2].t.x;
-        return (int)((h & 1u) ? (pair >> 16) : (pair & 0xffffu));
+    static __device__ __forceinline__ int count(const uint4& u, int j) {
+        const uint32_t d = word(u, j);
+        return (j & 1) ? (int)(d >> 28) : (int)__builtin_amdgcn_ubfe(d, 12, 4);
     }
 };
 
-// 4 bytes per entry: uint32 entries[round4(nnz)], entry = count << 18 | topic << 2, so that the
-// low 18 bits are the topic's key.  Usable when no document has 16384 tokens or more.
-struct PackedRows {
-    static constexpr int kEntryBytes = 4;
-    static constexpr int kWavesPerSimd = 6;
-    static constexpr int kMaxCount = (1 << 14) - 1;
-    struct Raw {
-        uint4 e;
-    };
-    // Every lane loads: a lane without entries reads the four padding entries that the
-    // library keeps in the first 16 bytes of the slot buffer (no slot starts there).
-    static __device__ __forceinline__ Raw load(const unsigned char* slots, uint32_t off, int,
-                                               int e, bool on, int) {
-        static_assert(kRowHeader == 16, "a row's entries start one 16-byte unit into its slot");
-        uint32_t unit = on ? off + 1u + ((uint32_t)e >> 2) : 0u;
-        // the choice is made on the 32-bit unit number, before it becomes a 64-bit address
-        asm volatile("" : "+v"(unit));
-        Raw q;
-        q.e = *reinterpret_cast<const uint4*>(slots + (size_t)unit * 16u);
-        return q;
-    }
-    static __device__ __forceinline__ uint32_t entry(const Raw& q, int j) {
-        return j == 0 ? q.e.x : j == 1 ? q.e.y : j == 2 ? q.e.z : q.e.w;
-    }
-    static __device__ __forceinline__ int count(const Raw& q, int j) { return (int)(entry(q, j) >> 18); }
-    static __device__ __forceinline__ int key(const Raw& q, int j) { return (int)(entry(q, j) & 0x3fffcu); }
-    static __device__ __forceinline__ uint32_t handle(const Raw* raw, int i) {
-        return entry(raw[i / 4], i % 4);
-    }
-    template <int kQuads>
-    static __device__ __forceinline__ int topic_of(const Raw*, uint32_t h) {
-        return (int)((h >> 2) & 0xffffu);
-    }
-};
+// Unit `unit` of the row in slot `off`.  Every lane loads: a lane without entries reads the
+// padding entries that the library keeps in the first 16 bytes of the slot buffer (no slot
+// starts there).
+__device__ __forceinline__ uint4 load_unit(const unsigned char* slots, uint32_t off, int unit, bool on) {
+    static_assert(kRowHeader == 16, "a row's entries start one 16-byte unit into its slot");
+    uint32_t at = on ? off + 1u + (uint32_t)unit : 0u;
+    // the choice is made on the 32-bit unit number, before it becomes a 64-bit address
+    asm volatile("" : "+v"(at));
+    return *reinterpret_cast<const uint4*>(slots + (size_t)at * 16u);
+}
+
+// Key of the entry that lies just before a unit in memory (a row's header ends in a padding
+// entry, so this is always an entry).
+template <class Layout>
+__device__ __forceinline__ int key_before_unit(const unsigned char* unit_ptr) {
+    typedef typename Layout::Entry Entry;
+    return 4 * Layout::entry_topic(*reinterpret_cast<const Entry*>(unit_ptr - sizeof(Entry)));
+}
 
 // p*(k) is staged at the very start of the workgroup's LDS, so a topic's key (4 k) is the
 // LDS address of its weight.
@@ -258,45 +279,70 @@ __device__ __forceinline__ float lds_float_at(uint32_t byte_address) {
     return *(lds_float_ptr)(uintptr_t)byte_address;
 }
 
-// p1 = (count - [k = o]) * p*'(k), Eq. 6, accumulated onto `base`:
-// s[j] = base + p1_0 + .. + p1_j (each product is exact in fp64).
-struct QuadSums {
-    double s[4];
-};
-
+// p1 = theta' p*' over the entries of one unit (Eq. 6), accumulated onto `acc` in entry order
+// (each product is exact in fp64).  The token's own topic o weighs w_o in all its entries and
+// its first entry counts one less: the token itself.  `prev_own`: the lanes whose entry before
+// this unit belongs to their o; on return: those whose last entry of the unit does.  ("Own and
+// first" is worked out on these lane masks, by the scalar unit.)
+// This form leaves the sum at the unit's end only: every entry is added with its whole count,
+// and the lanes whose first own entry lies in the unit give w_o back once, at the end.
 template <class Layout>
-__device__ __forceinline__ QuadSums quad_sums(const typename Layout::Raw& raw, int o_key, float w_o,
-                                              const float* pstar, double base) {
-    QuadSums q;
-    int key[4];
-    float w[4];
+__device__ __forceinline__ void unit_sum(const uint4& raw, int o_key, float w_o, uint64_t& prev_own,
+                                         double& acc) {
+    constexpr int n = Layout::kUnitEntries;
+    uint64_t first_here = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        key[j] = Layout::key(raw, j);
-        w[j] = lds_float_at((uint32_t)key[j]);
-    }
-    double acc = base;
+    for (int h = 0; h < n; h += 4) {       // four gathers of p* on their way at a time
+        int key[4];
+        float w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const bool own = key[j] == o_key;
-        acc = fma((double)(Layout::count(raw, j) - (own ? 1 : 0)), (double)(own ? w_o : w[j]), acc);
-        q.s[j] = acc;
+        for (int j = 0; j < 4; ++j) {
+            key[j] = Layout::key(raw, h + j);
+            w[j] = lds_float_at((uint32_t)key[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool own = key[j] == o_key;
+            const uint64_t own_lanes = __ballot(own);
+            first_here |= own_lanes & ~prev_own;
+            prev_own = own_lanes;
+            acc = fma((double)Layout::count(raw, h + j), (double)(own ? w_o : w[j]), acc);
+        }
     }
-    return q;
+    acc -= __builtin_amdgcn_inverse_ballot_w64(first_here) ? (double)w_o : 0.0;
 }
 
-// What the lanes of a group need of their token, read back from its record.
+// The same with the running sum after every entry and the entries' keys kept (the first own
+// entry counts one less where it stands).
+template <class Layout>
+__device__ __forceinline__ void unit_prefix_sums(const uint4& raw, int o_key, float w_o, uint64_t& prev_own,
+                                                 double& acc, double* sums, int* keys) {
+    constexpr int n = Layout::kUnitEntries;
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+        const int key = Layout::key(raw, j);
+        const bool own = key == o_key;
+        const uint64_t own_lanes = __ballot(own);
+        const bool first = __builtin_amdgcn_inverse_ballot_w64(own_lanes & ~prev_own);
+        prev_own = own_lanes;
+        acc = fma((double)(Layout::count(raw, j) - (first ? 1 : 0)),
+                  (double)(own ? w_o : lds_float_at((uint32_t)key)), acc);
+        sums[j] = acc;
+        keys[j] = key;
+    }
+}
+
+// What the lanes of a group need of their token for the walk, read back from its record.
 struct RowCtx {
+    uint32_t off;           // slot of the row
     int o_key;              // 4 * current topic (a topic's key is its byte offset in p*)
     float w_o;
-    double u, Qp;
 };
 
 __device__ __forceinline__ RowCtx row_ctx(const TokenRec* rec) {
-    const int2 ow = *reinterpret_cast<const int2*>(&rec->o);
-    const double2 uq = *reinterpret_cast<const double2*>(&rec->u);
+    const int4 head = *reinterpret_cast<const int4*>(rec);
     RowCtx r;
-    r.o_key = ow.x << 2; r.w_o = __int_as_float(ow.y); r.u = uq.x; r.Qp = uq.y;
+    r.off = (uint32_t)head.x; r.o_key = head.z << 2; r.w_o = __int_as_float(head.w);
     return r;
 }
 
@@ -307,104 +353,200 @@ struct RowDraw {
 };
 
 template <int kLanes>
-__device__ __forceinline__ RowDraw row_draw(double lane_sum, const RowCtx& r, int sl, int lane) {
+__device__ __forceinline__ RowDraw row_draw(double lane_sum, const TokenRec* rec, int sl, int lane) {
     RowDraw d;
     const double incl = group_inclusive_sum<kLanes>(lane_sum);
     const double excl = group_previous<kLanes>(incl, sl);
+    // (the lane that holds the group's total is worked out here, every time: hoisted out of
+    // the loop over passes, one such constant per shape would each hold a register for good)
+    asm volatile("" : "+v"(lane));
     d.S = __shfl(incl, group_last_lane<kLanes>(lane), kWave);
-    d.x = r.u * (d.S + r.Qp);
+    const double2 uq = *reinterpret_cast<const double2*>(&rec->u);     // the uniform, and Q'
+    d.x = uq.x * (d.S + uq.y);
     d.sparse = d.x < d.S;
     d.hit = d.sparse && (incl > d.x) && !(excl > d.x);
     d.y = d.x - excl;
     return d;
 }
 
-// The result goes back in the token's record.  Records of a batch's unused tail take part
-// like any other (their rows are empty): what is written there is never read.
-__device__ __forceinline__ void row_store(TokenRec* rec, int sl, const RowDraw& d, int k_sel) {
-    if (d.hit) rec->off = (uint32_t)k_sel;
+// A token whose draw falls into the dense bucket p2: recorded once, by its first sub-lane.
+__device__ __forceinline__ void record_dense(TokenRec* rec, int sl, const RowDraw& d) {
     if (!d.sparse && sl == 0) {
-        rec->off = 0xffffffffu;             // the draw falls into the dense bucket p2
+        rec->nnz = kDrawDense;
         rec->u = d.x - d.S;
     }
 }
 
-// Rows whose sub-lanes own at most kQuads quads, already loaded: every lane keeps its prefix
-// sums in registers, and the entries as loaded.
-template <class Layout, int kLanes, int kQuads>
-__device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, const typename Layout::Raw* raw,
-                                              const float* pstar, int lane) {
+// Rows whose sub-lanes own at most kUnits units, already loaded (`first_unit`: the lane's first
+// unit inside the row).  Every lane keeps its sum at the end of each unit; the lane that holds
+// the draw records which unit holds it and the rest of the draw there.
+// Rows with one entry per topic, already loaded: every lane keeps the running sum after each of
+// its entries, and the lane that holds the draw finds its entry at once.
+template <class Layout, int kLanes, int kUnits>
+__device__ __forceinline__ void row_pass_searched(TokenRec* rec, int sl, const uint4* raw, int lane) {
+    constexpr int UE = Layout::kUnitEntries, n = kUnits * UE;
     const RowCtx r = row_ctx(rec);
-    QuadSums q[kQuads];
+    double sums[n];
     double acc = 0.0;
 #pragma unroll
-    for (int c = 0; c < kQuads; ++c) {
-        q[c] = quad_sums<Layout>(raw[c], r.o_key, r.w_o, pstar, acc);
-        acc = q[c].s[3];
-    }
-    const RowDraw d = row_draw<kLanes>(acc, r, sl, lane);
-    // smallest entry whose prefix exceeds y (the prefixes never decrease)
-    uint32_t sel = Layout::handle(raw, 4 * kQuads - 1);
+    for (int c = 0; c < kUnits; ++c) {
+        int key[UE];
+        float w[UE];
 #pragma unroll
-    for (int i = 4 * kQuads - 2; i >= 0; --i)
-        if (q[i / 4].s[i % 4] > d.y) sel = Layout::handle(raw, i);
-    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no prefix above the draw:
+        for (int j = 0; j < UE; ++j) {
+            key[j] = Layout::key(raw[c], j);
+            w[j] = lds_float_at((uint32_t)key[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < UE; ++j) {
+            const bool own = key[j] == r.o_key;
+            acc = fma((double)(Layout::count(raw[c], j) - (own ? 1 : 0)), (double)(own ? r.w_o : w[j]), acc);
+            sums[c * UE + j] = acc;
+        }
+    }
+    const RowDraw d = row_draw<kLanes>(acc, rec, sl, lane);
+    // smallest entry whose sum exceeds y (the sums never decrease)
+    uint32_t entry = Layout::word(raw[kUnits - 1], UE - 1);
+#pragma unroll
+    for (int i = n - 2; i >= 0; --i)
+        if (sums[i] > d.y) entry = Layout::word(raw[i / UE], i % UE);
+    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no sum above the draw:
         if (d.hit && !(acc > d.y)) {                 // take the lane's last entry with weight
             double before = 0.0;
 #pragma unroll
-            for (int i = 0; i < 4 * kQuads; ++i) {
-                if (q[i / 4].s[i % 4] > before) sel = Layout::handle(raw, i);
-                before = q[i / 4].s[i % 4];
+            for (int i = 0; i < n; ++i) {
+                if (sums[i] > before) entry = Layout::word(raw[i / UE], i % UE);
+                before = sums[i];
             }
         }
     }
-    row_store(rec, sl, d, Layout::template topic_of<kQuads>(raw, sel));
+    if (d.hit) {
+        rec->off = (uint32_t)Layout::entry_topic(entry);
+        rec->nnz = kDrawTopic;
+    }
+    record_dense(rec, sl, d);
 }
 
-// Rows of more than 768 entries, one per wave (sub-lane = lane): one walk for the sums, a
-// second one over the hit lane's entries.  Lane l owns the entries [4 n4 l, 4 n4 (l + 1)).
-template <class Layout>
-__device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenRec* rec, int K,
-                                              const float* pstar, int lane) {
-    const uint2 where = *reinterpret_cast<const uint2*>(rec);
-    const uint32_t off = where.x;
-    const int nnz = (int)where.y, n4 = (nnz + 4 * kWave - 1) / (4 * kWave);
+template <class Layout, int kLanes, int kUnits>
+__device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, int first_unit, const uint4* raw,
+                                              int lane) {
+    if constexpr (Layout::kOneEntryPerTopic) {
+        row_pass_searched<Layout, kLanes, kUnits>(rec, sl, raw, lane);
+        return;
+    }
     const RowCtx r = row_ctx(rec);
-    const int e0 = lane * 4 * n4;
+    // does the entry before this lane's first one belong to the token's own topic?  (the
+    // previous sub-lane's last entry; a sub-lane past the row's end holds padding entries)
+    const int before = group_previous_int<kLanes>(Layout::key(raw[kUnits - 1], Layout::kUnitEntries - 1));
+    uint64_t prev_own = __ballot(sl > 0 && before == r.o_key);
+    double at_end[kUnits];
     double acc = 0.0;
-    for (int c = 0; c < n4; ++c) {
-        const int e = e0 + 4 * c;
-        const QuadSums q = quad_sums<Layout>(Layout::load(slots, off, nnz, e, e < nnz, K),
-                                             r.o_key, r.w_o, pstar, acc);
-        acc = q.s[3];
-    }
-    const RowDraw d = row_draw<kWave>(acc, r, lane, lane);
-    int k_sel = 0;
-    if (__ballot(d.hit) != 0) {
-        bool ok = false;
-        int last_k = 0;
-        acc = 0.0;
-        for (int c = 0; c < n4; ++c) {
-            const int e = e0 + 4 * c;
-            const typename Layout::Raw raw = Layout::load(slots, off, nnz, e, d.hit && e < nnz, K);
-            const QuadSums q = quad_sums<Layout>(raw, r.o_key, r.w_o, pstar, acc);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const double before = (j == 0) ? acc : q.s[j - 1];
-                if (!ok && q.s[j] > d.y) { k_sel = Layout::key(raw, j) >> 2; ok = true; }
-                if (q.s[j] > before) last_k = Layout::key(raw, j) >> 2;
-            }
-            acc = q.s[3];
-        }
-        if (!ok) k_sel = last_k;
+    for (int c = 0; c < kUnits; ++c) {
+        unit_sum<Layout>(raw[c], r.o_key, r.w_o, prev_own, acc);
+        at_end[c] = acc;
     }
-    row_store(rec, lane, d, k_sel);
+    const RowDraw d = row_draw<kLanes>(acc, rec, sl, lane);
+    // first unit whose end exceeds y (the sums never decrease), and the sum before it
+    int unit = kUnits - 1;
+#pragma unroll
+    for (int c = kUnits - 2; c >= 0; --c)
+        if (at_end[c] > d.y) unit = c;
+    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no sum above the draw:
+        if (d.hit && !(acc > d.y)) {                 // take the lane's last unit with weight
+            double before_unit = 0.0;
+#pragma unroll
+            for (int c = 0; c < kUnits; ++c) {
+                if (at_end[c] > before_unit) unit = c;
+                before_unit = at_end[c];
+            }
+        }
+    }
+    double base = 0.0;
+#pragma unroll
+    for (int c = 1; c < kUnits; ++c)
+        if (unit >= c) base = at_end[c - 1];
+    if (d.hit) {
+        rec->off = r.off + 1u + (uint32_t)(first_unit + unit);
+        rec->nnz = kDrawInUnit;
+        rec->u = d.y - base;
+    }
+    record_dense(rec, sl, d);
+}
+
+// The entry of one unit that holds the draw y (measured from the unit's start): the first
+// whose running sum exceeds y, else (rounding) the last one with weight.  One token per lane.
+template <class Layout>
+__device__ __forceinline__ int topic_in_unit(const unsigned char* slots, uint32_t unit, int o_key,
+                                             float w_o, double y) {
+    constexpr int n = Layout::kUnitEntries;
+    const unsigned char* p = slots + (size_t)unit * 16u;
+    const uint4 raw = *reinterpret_cast<const uint4*>(p);
+    uint64_t prev_own = __ballot(key_before_unit<Layout>(p) == o_key);
+    double acc = 0.0;
+    int found = -1, last = Layout::key(raw, 0);     // keys: the first above y, the last with weight
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+        const int key = Layout::key(raw, j);
+        const uint64_t own_lanes = __ballot(key == o_key);
+        const bool own = __builtin_amdgcn_inverse_ballot_w64(own_lanes);
+        const bool first = __builtin_amdgcn_inverse_ballot_w64(own_lanes & ~prev_own);
+        prev_own = own_lanes;
+        const double before = acc;
+        acc = fma((double)(Layout::count(raw, j) - (first ? 1 : 0)),
+                  (double)(own ? w_o : lds_float_at((uint32_t)key)), acc);
+        if (acc > before) last = key;
+        if (found < 0 && acc > y) found = key;
+    }
+    return (found >= 0 ? found : last) >> 2;
+}
+
+// Rows too long for the kept shapes, one per wave (sub-lane = lane): one walk for the sums, a
+// second one over the hit lane's entries.  Lane l owns the units [n l, n (l + 1)).
+template <class Layout>
+__device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenRec* rec, int lane) {
+    constexpr int UE = Layout::kUnitEntries;
+    const RowCtx r = row_ctx(rec);
+    const int nnz = rec->nnz;
+    const int n_units = (nnz + UE - 1) / UE, n = (n_units + kWave - 1) / kWave;
+    const int u0 = lane * n;
+    // the entry before the lane's first one (lanes past the row's end have no entries at all)
+    const bool own_before = u0 < n_units &&
+        key_before_unit<Layout>(slots + ((size_t)r.off + 1u + (size_t)u0) * 16u) == r.o_key;
+    uint64_t prev_own = __ballot(own_before);
+    double acc = 0.0;
+    for (int c = 0; c < n; ++c)
+        unit_sum<Layout>(load_unit(slots, r.off, u0 + c, u0 + c < n_units), r.o_key, r.w_o, prev_own, acc);
+    const RowDraw d = row_draw<kWave>(acc, rec, lane, lane);
+    if (__ballot(d.hit) != 0) {
+        bool found = false;
+        int k_sel = 0, last_k = 0;
+        prev_own = __ballot(own_before);
+        acc = 0.0;
+        for (int c = 0; c < n; ++c) {
+            double sums[UE];
+            int keys[UE];
+            const double before_unit = acc;
+            unit_prefix_sums<Layout>(load_unit(slots, r.off, u0 + c, d.hit && u0 + c < n_units), r.o_key,
+                                     r.w_o, prev_own, acc, sums, keys);
+#pragma unroll
+            for (int j = 0; j < UE; ++j) {
+                const double before = (j == 0) ? before_unit : sums[j - 1];
+                if (!found && sums[j] > d.y) { k_sel = keys[j] >> 2; found = true; }
+                if (sums[j] > before) last_k = keys[j] >> 2;
+            }
+        }
+        if (d.hit) {
+            rec->off = (uint32_t)(found ? k_sel : last_k);
+            rec->nnz = kDrawTopic;
+        }
+    }
+    record_dense(rec, lane, d);
 }
 
 template <int kWaves, class Layout>
-// Six waves per SIMD (80 VGPRs) with 4-byte entries, five (96 VGPRs) with 6-byte entries,
-// whose quads take half as many registers again: the walk hides HBM latency by occupancy as
-// well as by the early loads.
+// Six waves per SIMD (80 VGPRs): the walk hides HBM latency by occupancy as well as by the
+// early loads.
 __attribute__((amdgpu_waves_per_eu(Layout::kWavesPerSimd)))
 __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -466,7 +608,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     __syncthreads();
 
     // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
-    // place inside its group, its first quad of entries
+    // place inside its group, its first unit of entries
     int geo_shape = -1, geo_rel = 0, geo_sl = 0, geo_q0 = 0;
     // A wave takes up to 64 tokens at a time.  A tile too small to give every wave such a batch
     // is dealt out in smaller batches, so that all waves work on it side by side: the passes
@@ -507,65 +649,66 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // ---- one token per group of 4 .. 64 lanes.  A pass takes the next 16, 8, 4, 2 or 1
-        // tokens, as many as lets every lane own at most kKeptQuads quads; the rows of the
+        // tokens, as many as lets every lane own at most kKeptUnits units; the rows of the
         // following pass are requested from memory before this one is worked on.
-        // Shapes of a pass (lanes per token, quads per lane -> entries per row at most):
-        //   0 (4,1) 16   1 (4,2) 32   2 (8,2) 64   3 (8,3) 96   4 (16,2) 128   5 (16,3) 192
-        //   6 (32,2) 256   7 (32,3) 384   8 (64,2) 512   9 (64,3) 768
-        //   10 = one longer row, walked twice by the wave
+        // Shapes of a pass (lanes per token, units per lane); a row may have up to
+        // lanes * units * (entries per unit) entries:
+        //   0 (4,1)   1 (4,2)   2 (4,3)   3 (8,2)   4 (8,3)   5 (16,2)   6 (16,3)
+        //   7 (32,2)   8 (32,3)   9 (64,2)   10 (64,3)   11 = one longer row, walked twice by the wave
         // Which tokens of the batch have rows beyond each of these lengths (lanes past the
         // batch's end hold nnz = 0): the shape of every pass follows from these masks.
         const int n_here = min(batch, tl.count - b * batch);
-        static_assert(kKeptQuads == 3, "the pass shapes assume three kept quads per lane");
-        const uint64_t over16 = __ballot(mine.nnz > 16), over32 = __ballot(mine.nnz > 32);
-        const uint64_t over64 = __ballot(mine.nnz > 64), over96 = __ballot(mine.nnz > 96);
-        const uint64_t over128 = __ballot(mine.nnz > 128), over192 = __ballot(mine.nnz > 192);
-        const uint64_t over256 = __ballot(mine.nnz > 256), over384 = __ballot(mine.nnz > 384);
-        const uint64_t over512 = __ballot(mine.nnz > 512), over768 = __ballot(mine.nnz > 768);
+        static_assert(kKeptUnits == 3, "the pass shapes assume three kept units per lane");
+        constexpr int UE = Layout::kUnitEntries;
+        const uint64_t over_4_1 = __ballot(mine.nnz > 4 * UE), over_4_2 = __ballot(mine.nnz > 8 * UE);
+        const uint64_t over_4_3 = __ballot(mine.nnz > 12 * UE), over_8_2 = __ballot(mine.nnz > 16 * UE);
+        const uint64_t over_8_3 = __ballot(mine.nnz > 24 * UE), over_16_2 = __ballot(mine.nnz > 32 * UE);
+        const uint64_t over_16_3 = __ballot(mine.nnz > 48 * UE), over_32_2 = __ballot(mine.nnz > 64 * UE);
+        const uint64_t over_32_3 = __ballot(mine.nnz > 96 * UE), over_64_2 = __ballot(mine.nnz > 128 * UE);
+        const uint64_t over_64_3 = __ballot(mine.nnz > 192 * UE);
         auto any = [](uint64_t mask, int t0, uint32_t window) {      // 1 if a token of the window is set
             const uint32_t w = (uint32_t)(mask >> t0) & window;
             return min(1, (int)__builtin_popcount(w));      // stays scalar arithmetic
         };
         auto shape_at = [&](int t0) {
-            if (!any(over32, t0, 0xffffu)) return any(over16, t0, 0xffffu);
-            if (!any(over96, t0, 0xffu)) return 2 + any(over64, t0, 0xffu);
-            if (!any(over192, t0, 0xfu)) return 4 + any(over128, t0, 0xfu);
-            if (!any(over384, t0, 0x3u)) return 6 + any(over256, t0, 0x3u);
-            if (!any(over768, t0, 0x1u)) return 8 + any(over512, t0, 0x1u);
-            return 10;
+            if (!any(over_4_3, t0, 0xffffu)) return any(over_4_1, t0, 0xffffu) + any(over_4_2, t0, 0xffffu);
+            if (!any(over_8_3, t0, 0xffu)) return 3 + any(over_8_2, t0, 0xffu);
+            if (!any(over_16_3, t0, 0xfu)) return 5 + any(over_16_2, t0, 0xfu);
+            if (!any(over_32_3, t0, 0x3u)) return 7 + any(over_32_2, t0, 0x3u);
+            if (!any(over_64_3, t0, 0x1u)) return 9 + any(over_64_2, t0, 0x1u);
+            return 11;
         };
-        auto lanes_log2 = [](int shape) { return (int)((0x66655443322ull >> (4 * shape)) & 0xfull); };
-        auto quads_of = [](int shape) { return (int)((0x03232323221ull >> (4 * shape)) & 0xfull); };
-        // where a pass's rows are, and the loads of the quads its lanes keep.  `rec` is the
+        auto lanes_log2 = [](int shape) { return (int)((0x666554433222ull >> (4 * shape)) & 0xfull); };
+        auto units_of = [](int shape) { return (int)((0x032323232321ull >> (4 * shape)) & 0xfull); };
+        // where a pass's rows are, and the loads of the units its lanes keep.  `rec` is the
         // record of the lane's token, `sl` the lane's place inside its group.  A pass that
         // would run past the batch's 64 records works on the last one several times over.
-        using Raw = typename Layout::Raw;
-        auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, Raw* raw) {
-            const int nq = quads_of(shape);
+        auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, uint4* raw) {
+            const int nu = units_of(shape);
             if (shape != geo_shape) {       // the lanes' places change only with the shape
                 const int lg = lanes_log2(shape);
                 const int g = lg < 4 ? 4 - lg : 0, hs = lg < 4 ? 4 : lg;    // interleave, run length
                 geo_shape = shape;
                 geo_rel = ((lane >> hs) << g) | (lane & ((1 << g) - 1));
                 geo_sl = (lane & ((1 << hs) - 1)) >> g;
-                geo_q0 = geo_sl * nq;        // the lane's first quad
+                geo_q0 = geo_sl * nu;        // the lane's first unit
             }
             sl = geo_sl;
             rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
-            const int nnz = (int)where.y;
-            // quads the lane loads: those of the shape that the row still has from q0 on
-            const int n_mine = min(((nnz + 3) >> 2) - geo_q0, nq);
+            // units the lane loads: those of the shape that the row still has from its first on
+            const int n_mine = min((((int)where.y + UE - 1) / UE) - geo_q0, nu);
 #pragma unroll
-            for (int c = 0; c < kKeptQuads; ++c)
-                raw[c] = Layout::load(a.slots, where.x, nnz, 4 * (geo_q0 + c), c < n_mine, K);
+            for (int c = 0; c < kKeptUnits; ++c)
+                raw[c] = load_unit(a.slots, where.x, geo_q0 + c, c < n_mine);
         };
         int t_next = 0, shape_next = shape_at(0), sl_next;
         TokenRec* rec_next;
         // one pass: `mine_raw` holds its rows, already requested; the following pass's rows
         // go to `next_raw`.  The two buffers swap roles from pass to pass.
-        auto pass = [&](Raw* mine_raw, Raw* next_raw) {
+        auto pass = [&](uint4* mine_raw, uint4* next_raw) {
             const int shape = shape_next, sl = sl_next;
+            const int first_unit = sl * units_of(shape);
             TokenRec* rec = rec_next;
             t_next += kWave >> lanes_log2(shape);
             if (t_next < n_here) {
@@ -573,20 +716,21 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
                 request(t_next, shape_next, rec_next, sl_next, next_raw);
             }
             switch (shape) {
-            case 0: row_pass_kept<Layout, 4, 1>(rec, sl, mine_raw, pstar, lane); break;
-            case 1: row_pass_kept<Layout, 4, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 2: row_pass_kept<Layout, 8, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 3: row_pass_kept<Layout, 8, 3>(rec, sl, mine_raw, pstar, lane); break;
-            case 4: row_pass_kept<Layout, 16, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 5: row_pass_kept<Layout, 16, 3>(rec, sl, mine_raw, pstar, lane); break;
-            case 6: row_pass_kept<Layout, 32, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 7: row_pass_kept<Layout, 32, 3>(rec, sl, mine_raw, pstar, lane); break;
-            case 8: row_pass_kept<Layout, 64, 2>(rec, sl, mine_raw, pstar, lane); break;
-            case 9: row_pass_kept<Layout, 64, 3>(rec, sl, mine_raw, pstar, lane); break;
-            default: row_pass_long<Layout>(a.slots, rec, K, pstar, lane); break;
+            case 0: row_pass_kept<Layout, 4, 1>(rec, sl, first_unit, mine_raw, lane); break;
+            case 1: row_pass_kept<Layout, 4, 2>(rec, sl, first_unit, mine_raw, lane); break;
+            case 2: row_pass_kept<Layout, 4, 3>(rec, sl, first_unit, mine_raw, lane); break;
+            case 3: row_pass_kept<Layout, 8, 2>(rec, sl, first_unit, mine_raw, lane); break;
+            case 4: row_pass_kept<Layout, 8, 3>(rec, sl, first_unit, mine_raw, lane); break;
+            case 5: row_pass_kept<Layout, 16, 2>(rec, sl, first_unit, mine_raw, lane); break;
+            case 6: row_pass_kept<Layout, 16, 3>(rec, sl, first_unit, mine_raw, lane); break;
+            case 7: row_pass_kept<Layout, 32, 2>(rec, sl, first_unit, mine_raw, lane); break;
+            case 8: row_pass_kept<Layout, 32, 3>(rec, sl, first_unit, mine_raw, lane); break;
+            case 9: row_pass_kept<Layout, 64, 2>(rec, sl, first_unit, mine_raw, lane); break;
+            case 10: row_pass_kept<Layout, 64, 3>(rec, sl, first_unit, mine_raw, lane); break;
+            default: row_pass_long<Layout>(a.slots, rec, lane); break;
             }
         };
-        Raw raw_a[kKeptQuads], raw_b[kKeptQuads];
+        uint4 raw_a[kKeptUnits], raw_b[kKeptUnits];
         request(0, shape_next, rec_next, sl_next, raw_a);
         while (t_next < n_here) {
             pass(raw_a, raw_b);
@@ -596,18 +740,20 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- one token per lane again: dense bucket, store
+        // ---- one token per lane again: the entry inside the unit that holds the draw, or the
+        // dense bucket; store
         // (the token's topic and corrected weight are read back from its record rather than
         // kept in registers across the passes)
         if (lane < batch && b * batch + lane < tl.count) {
             const TokenRec* rec = &my_rec[lane];
-            int z_new = (int)rec->off;
-            if (z_new < 0) {
-                const int o = rec->o;
-                const float w_o = rec->w_o;
-                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, o, w_o,
-                                                    (double)w_o - (double)pstar[o]);
-            }
+            const int4 head = *reinterpret_cast<const int4*>(rec);     // off, kind, o, w_o
+            const float w_o = __int_as_float(head.w);
+            int z_new = head.x;
+            if (head.y == kDrawInUnit)
+                z_new = topic_in_unit<Layout>(a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
+            if (head.y == kDrawDense)
+                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, head.z, w_o,
+                                                    (double)w_o - (double)pstar[head.z]);
             a.z_next[tl.begin + b * batch + lane] = (uint16_t)z_new;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

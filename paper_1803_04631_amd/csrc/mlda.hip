@@ -54,12 +54,23 @@ constexpr size_t kSlotAlign = 64;     // theta row slot alignment (bytes)
 // (twelve: two such workgroups fill a CU's six waves per SIMD, and their LDS fits twice)
 int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 12; }
 
-const void* sample_kernel_for(int32_t K, bool packed) {
+// theta rows with 2-byte entries where the topics fit their ten bits
+bool tiny_rows_for(int32_t K) { return K <= mlda::TinyRows::kMaxK; }
+
+// short_docs: no document has more tokens than a 4-byte entry counts
+const void* sample_kernel_for(int32_t K, bool short_docs) {
+    if (tiny_rows_for(K)) return (const void*)mlda::sample_kernel<4, mlda::TinyRows>;
     if (sample_waves_for(K) == 4)
-        return packed ? (const void*)mlda::sample_kernel<4, mlda::PackedRows>
-                      : (const void*)mlda::sample_kernel<4, mlda::SplitRows>;
-    return packed ? (const void*)mlda::sample_kernel<12, mlda::PackedRows>
-                  : (const void*)mlda::sample_kernel<12, mlda::SplitRows>;
+        return short_docs ? (const void*)mlda::sample_kernel<4, mlda::PackedRowsShort>
+                          : (const void*)mlda::sample_kernel<4, mlda::PackedRows>;
+    return short_docs ? (const void*)mlda::sample_kernel<12, mlda::PackedRowsShort>
+                      : (const void*)mlda::sample_kernel<12, mlda::PackedRows>;
+}
+const void* theta_kernel_for(bool tiny, bool wide_counters) {
+    if (tiny) return wide_counters ? (const void*)mlda::theta_rows_kernel<mlda::TinyRows, true>
+                                   : (const void*)mlda::theta_rows_kernel<mlda::TinyRows, false>;
+    return wide_counters ? (const void*)mlda::theta_rows_kernel<mlda::PackedRows, true>
+                         : (const void*)mlda::theta_rows_kernel<mlda::PackedRows, false>;
 }
 constexpr int kMaxTimedIters = 1024;
 
@@ -68,10 +79,13 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
 constexpr int kPhiSegment = 16384;    // tokens one workgroup histograms for the phi rebuild
 
-// A theta row's slot: a header of kRowHeader bytes (the row's length), then the entries.
-size_t slot_bytes_for(int64_t cap, int entry_bytes) {   // cap = largest nnz the row can reach
-    return align_up((size_t)mlda::kRowHeader + (size_t)(((cap + 3) & ~(int64_t)3) * entry_bytes),
-                    kSlotAlign);
+// A theta row's slot: a header of kRowHeader bytes (the row's number of entries), then the
+// entries, filled up to whole 16-byte units.  A document of n tokens needs at most
+// min(n, K + n / max_count) entries: one per topic, and one more for every max_count tokens
+// that a count exceeds its entry's field by.
+size_t slot_bytes_for(int64_t n, int32_t K, int entry_bytes, int max_count) {
+    const int64_t cap = std::min<int64_t>(n, (int64_t)K + n / max_count);
+    return align_up((size_t)mlda::kRowHeader + align_up((size_t)cap * (size_t)entry_bytes, 16), kSlotAlign);
 }
 
 constexpr int kLoglikBlocks = 2048;
@@ -113,7 +127,8 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
 // An upper bound of the same from the sizes alone.
 ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
     const size_t tile = (size_t)tile_tokens_for(K);
-    const size_t slots = kSlotAlign + (size_t)T * 6 + (size_t)D * (mlda::kRowHeader + 18 + kSlotAlign);
+    // (at most one entry of at most 4 bytes per token, a header, a unit's and a slot's rounding)
+    const size_t slots = kSlotAlign + (size_t)T * 4 + (size_t)D * (mlda::kRowHeader + 16 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
     const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
     return chunk_layout(D, T, slots, n_tiles, n_segs, (size_t)V);
@@ -182,7 +197,9 @@ struct HostChunk {
     int64_t d_begin = 0, d_end = 0;
     int64_t tok_begin = 0;              // caller's index of the chunk's first token
     int64_t D = 0, T = 0;
-    bool packed = true;                 // theta rows as 4-byte entries (no document has 2^14 tokens)
+    bool tiny = false;                  // theta rows as 2-byte entries (K < 1024), else 4-byte
+    bool wide_counters = false;         // some document has 2^16 tokens or more
+    bool short_docs = true;             // no document has more tokens than a 4-byte entry counts
     size_t slots_bytes = 0;
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
     int32_t n_wide_tiles = 0;           // sampling tiles of words whose row of phi is int32
@@ -219,9 +236,13 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
 
     int64_t longest_doc = 0;
     for (int64_t d = 0; d < D; ++d) longest_doc = std::max(longest_doc, len_of(d));
-    // a count never exceeds the document's length: 4-byte theta entries if 14 bits hold it
-    h.packed = longest_doc <= mlda::PackedRows::kMaxCount;
-    const int entry_bytes = h.packed ? mlda::PackedRows::kEntryBytes : mlda::SplitRows::kEntryBytes;
+    h.tiny = tiny_rows_for(K);
+    // a count never exceeds the document's length: 16-bit counters in the theta rebuild if
+    // they hold it
+    h.wide_counters = longest_doc >= 65536;
+    h.short_docs = longest_doc <= mlda::PackedRows::kMaxCount;
+    const int entry_bytes = h.tiny ? mlda::TinyRows::kEntryBytes : mlda::PackedRows::kEntryBytes;
+    const int max_count = h.tiny ? mlda::TinyRows::kMaxCount : mlda::PackedRows::kMaxCount;
 
     std::vector<int32_t> doc_order;              // documents by falling length
     std::vector<int64_t> order_tokens;           // tokens before each position of doc_order
@@ -237,7 +258,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         order_tokens[0] = 0;
         for (int64_t i = 0; i < D; ++i)
             order_tokens[(size_t)i + 1] = order_tokens[(size_t)i] + len_of(doc_order[(size_t)i]);
-        // theta row slots: fixed capacity min(N_d, K), so rows never move; laid out in the
+        // theta row slots: fixed capacity, so rows never move; laid out in the
         // order the documents are worked on, so that rows in use together are neighbours.
         // The buffer starts with four padding entries.
         slot_of.resize((size_t)D);
@@ -246,7 +267,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
             const int64_t d = doc_order[(size_t)i];
             if (h.slots_bytes / 16 > 0xffffffffull) return fail(MLDA_ENOTSUP, "theta rows need more than 64 GiB");
             slot_of[(size_t)d] = (uint32_t)(h.slots_bytes / 16);
-            h.slots_bytes += slot_bytes_for(std::min<int64_t>(len_of(d), K), entry_bytes);
+            h.slots_bytes += slot_bytes_for(len_of(d), K, entry_bytes, max_count);
         }
         word_ptr.assign((size_t)V + 1, 0);
     } catch (const std::bad_alloc&) {
@@ -441,7 +462,7 @@ struct mlda_ctx {
     int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr, *block_doc = nullptr;
     mlda::DocRec* doc_order = nullptr;   // documents by falling length, as the theta rebuild walks them
     int32_t theta_grid = 0;
-    bool packed = false;
+    bool tiny = false, wide_counters = false, short_docs = true;
     int32_t* split_words = nullptr;
     uint16_t* z[2] = {nullptr, nullptr}; // word-major assignments
     uint16_t* z_doc = nullptr;           // streamed: the same in document order (in doc_map's place)
@@ -507,7 +528,9 @@ int blocks_for(int64_t n, int per) { return (int)((n + per - 1) / per); }
 void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->at = &h;
     c->D = h.D; c->T = h.T;
-    c->packed = h.packed;
+    c->tiny = h.tiny;
+    c->wide_counters = h.wide_counters;
+    c->short_docs = h.short_docs;
     c->slots_bytes = h.slots_bytes;
     c->n_tiles = h.n_tiles; c->n_segs = h.n_segs; c->n_split = h.n_split;
     c->n_wide_tiles = h.n_wide_tiles;
@@ -526,7 +549,7 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->z[1] = (uint16_t*)(base + h.L.z1);
     c->slots = base + h.L.slots;
     c->cur = 0;
-    const size_t theta_lds = mlda::theta_lds_bytes(c->K, h.packed);
+    const size_t theta_lds = mlda::theta_lds_bytes(c->K, h.wide_counters);
     // 16 one-wave workgroups per CU: enough to hide the gathers' latency; more of them
     // touch more lines of z at once than an XCD's L2 holds, and neighbours stop sharing
     const int per_cu = std::max(1, std::min(16, (int)(144 * 1024 / theta_lds)));
@@ -554,8 +577,10 @@ void derive_chunk_arrays(mlda_ctx* c) {
         hipLaunchKernelGGL(mlda::derive_tok_slot_kernel, dim3((unsigned)grid), dim3(mlda::kWave), 0, c->stream,
                            c->doc_order, c->D, c->doc_map, c->tok_slot);
     }
+    const uint32_t pad = c->tiny ? (uint32_t)mlda::TinyRows::make(0, c->K) * 0x10001u
+                                 : (uint32_t)mlda::PackedRows::make(0, c->K);
     hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(1), dim3(256), 0, c->stream, (int32_t*)c->slots,
-                       (int64_t)4, (int32_t)((uint32_t)c->K << 2));
+                       (int64_t)4, (int32_t)pad);
 }
 
 // Streamed: bring chunk m into the slot of this visit.  The static part (and with_z: the
@@ -674,25 +699,25 @@ int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
     using namespace mlda;
     const int32_t* doc_map = c->streamed ? nullptr : c->doc_map;
     if (c->D > 0) {
-        const size_t theta_lds = theta_lds_bytes(c->K, c->packed);
+        const size_t theta_lds = theta_lds_bytes(c->K, c->wide_counters);
         unsigned long long* entries = c->row_entries + (c->rebuilds % kEntryRing);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, c->stream, entries);
         // two documents per wave where a half-wave suits them: few topics, short documents
-        if (c->packed && c->K <= kPairMaxK && c->T <= 160 * c->D)
-            hipLaunchKernelGGL(theta_rows_pair_kernel, dim3((unsigned)c->theta_grid), dim3(kWave),
-                               2 * theta_hist_bytes(c->K, true) + (size_t)kThetaLgTable * 8, c->stream,
-                               c->doc_order, doc_map, z, c->row_rec, c->slots, c->D, c->K, c->alpha,
-                               c->lg_table, entries, c->ll_partial + 2 * kLoglikBlocks);
-        else if (c->packed)
-            hipLaunchKernelGGL(theta_rows_kernel<true>, dim3((unsigned)c->theta_grid), dim3(kWave),
-                               theta_lds, c->stream, c->doc_order, doc_map, z, c->row_rec, c->slots,
-                               c->D, c->K, c->alpha, c->lg_table, entries,
-                               c->ll_partial + 2 * kLoglikBlocks);
-        else
-            hipLaunchKernelGGL(theta_rows_kernel<false>, dim3((unsigned)c->theta_grid), dim3(kWave),
-                               theta_lds, c->stream, c->doc_order, doc_map, z, c->row_rec, c->slots,
-                               c->D, c->K, c->alpha, c->lg_table, entries,
-                               c->ll_partial + 2 * kLoglikBlocks);
+        const bool pairs = c->K <= kPairMaxK && !c->wide_counters && c->T <= 160 * c->D;
+        const void* kernel =
+            pairs ? (c->tiny ? (const void*)theta_rows_pair_kernel<TinyRows> : (const void*)theta_rows_pair_kernel<PackedRows>)
+                  : theta_kernel_for(c->tiny, c->wide_counters);
+        const size_t lds = pairs ? 2 * theta_hist_bytes(c->K, false) + (size_t)kThetaLgTable * 8 : theta_lds;
+        const DocRec* docs = c->doc_order;
+        uint2* row_rec = c->row_rec;
+        unsigned char* slots = c->slots;
+        int64_t D = c->D;
+        int32_t K = c->K;
+        double alpha = c->alpha;
+        const double* lg_table = c->lg_table;
+        double* ll_partial = c->ll_partial + 2 * kLoglikBlocks;
+        void* args[] = {&docs, &doc_map, &z, &row_rec, &slots, &D, &K, &alpha, &lg_table, &entries, &ll_partial};
+        HIP_TRY(hipLaunchKernel(kernel, dim3((unsigned)c->theta_grid), dim3(kWave), args, lds, c->stream));
     }
     c->rebuilds += 1;
     return launch_check("theta rebuild kernel");
@@ -718,7 +743,7 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     a.iter = (uint32_t)(c->iter + 1);
     const int waves = sample_waves_for(c->K);
     void* kernel_args[] = {&a};
-    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->packed), dim3((unsigned)c->n_tiles),
+    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs), dim3((unsigned)c->n_tiles),
                             dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
     return launch_check("sample_kernel");
 }
@@ -842,22 +867,21 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(blocks_for(dwords, 256)), dim3(256), 0, c->stream,
                        (int32_t*)c->phi[0].narrow, dwords, 0);
     RC_TRY(launch_check("model set-up kernels"));
-    const void* samplers[] = {sample_kernel_for(c->K, true), sample_kernel_for(c->K, false)};
     if (c->sample_lds > 48 * 1024)
-        for (const void* k : samplers)
-            HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->sample_lds));
+        for (bool short_docs : {false, true})
+            HIP_TRY(hipFuncSetAttribute(sample_kernel_for(c->K, short_docs),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->sample_lds));
     if ((size_t)c->K * 4 > 48 * 1024) {
         HIP_TRY(hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
         HIP_TRY(hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
-        HIP_TRY(hipFuncSetAttribute((const void*)mlda::theta_rows_kernel<true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)mlda::theta_lds_bytes(c->K, true)));
-        HIP_TRY(hipFuncSetAttribute((const void*)mlda::theta_rows_kernel<false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)mlda::theta_lds_bytes(c->K, false)));
     }
+    for (bool wide : {false, true})
+        if (mlda::theta_lds_bytes(c->K, wide) > 48 * 1024)
+            HIP_TRY(hipFuncSetAttribute(theta_kernel_for(tiny_rows_for(c->K), wide),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)mlda::theta_lds_bytes(c->K, wide)));
     return MLDA_OK;
 }
 
@@ -963,23 +987,37 @@ int fetch_row_rec(mlda_ctx* c, std::vector<uint2>& rec) {
     return MLDA_OK;
 }
 
-void unpack_rows(const mlda_ctx* c, const std::vector<uint2>& rec, const std::vector<unsigned char>& slots,
-                 const int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
+// rec[d].y = distinct topics of row d (the length of its CSR row); the slot's header holds the
+// number of entries, of which several in a row may share a topic (a count spread over them).
+template <class Layout>
+void unpack_rows_as(const mlda_ctx* c, const std::vector<uint2>& rec, const std::vector<unsigned char>& slots,
+                    const int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
+    typedef typename Layout::Entry Entry;
     for (int64_t d = 0; d < c->D; ++d) {
-        const uint32_t nnz = rec[(size_t)d].y, pad = (nnz + 3u) & ~3u;
-        const unsigned char* base = slots.data() + (size_t)rec[(size_t)d].x * 16 + mlda::kRowHeader;
-        if (nnz == 0) continue;
-        if (c->packed) {
-            const uint32_t* ent = reinterpret_cast<const uint32_t*>(base);
-            for (uint32_t j = 0; j < nnz; ++j) {
-                counts[row_ptr[d] + j] = (int32_t)(ent[j] >> 18);
-                topics[row_ptr[d] + j] = (uint16_t)((ent[j] >> 2) & 0xffffu);
+        if (rec[(size_t)d].y == 0) continue;
+        const unsigned char* head = slots.data() + (size_t)rec[(size_t)d].x * 16;
+        uint32_t n_entries;
+        std::memcpy(&n_entries, head, 4);
+        const Entry* ent = reinterpret_cast<const Entry*>(head + mlda::kRowHeader);
+        int64_t at = row_ptr[d] - 1;
+        int last_topic = -1;
+        for (uint32_t j = 0; j < n_entries; ++j) {
+            const int topic = Layout::entry_topic(ent[j]), count = Layout::entry_count(ent[j]);
+            if (topic != last_topic) {
+                ++at;
+                topics[at] = (uint16_t)topic;
+                counts[at] = 0;
+                last_topic = topic;
             }
-        } else {
-            std::memcpy(counts + row_ptr[d], base, (size_t)nnz * 4);
-            std::memcpy(topics + row_ptr[d], base + (size_t)pad * 4, (size_t)nnz * 2);
+            counts[at] += count;
         }
     }
+}
+
+void unpack_rows(const mlda_ctx* c, const std::vector<uint2>& rec, const std::vector<unsigned char>& slots,
+                 const int64_t* row_ptr, uint16_t* topics, int32_t* counts) {
+    if (c->tiny) unpack_rows_as<mlda::TinyRows>(c, rec, slots, row_ptr, topics, counts);
+    else unpack_rows_as<mlda::PackedRows>(c, rec, slots, row_ptr, topics, counts);
 }
 
 // Streamed: phi and n_k of the assignments in z_host (after init or set_assignments);
@@ -1476,7 +1514,7 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
         // per token: row slot 4, token id 4, old topic 2, new topic 2, row length 4
         // per tile: the word's row of phi, 2 K bytes, or 4 K for a word with 2^16 tokens or more
-        bytes[i] = 16.0 * (double)c->T + (c->packed ? 4.0 : 6.0) * row_entries +
+        bytes[i] = 16.0 * (double)c->T + (c->tiny ? 2.0 : 4.0) * row_entries +
                    (double)c->K * (2.0 * (double)c->n_tiles + 2.0 * (double)c->n_wide_tiles);
     }
     *n_iters = n;

@@ -115,12 +115,15 @@ EDGE_CASES = [
     ("short_docs",          3000, 200, 16,  1.2),     # many single-token documents (S = 0)
     ("k_twenty_thousand",   40,  300,  20000, 400),   # every kernel beyond 64 KB of LDS
     ("k_near_lds_limit",    40,  300,  30800, 400),   # 160 KB of LDS: one workgroup per CU
-    # documents of 2^14 tokens or more: the library falls back to 6-byte theta entries
+    # long documents over few topics: counts far beyond one entry's field are spread over
+    # several entries of the same topic (2-byte entries hold counts up to 15)
     ("huge_docs_split_rows", 3,   400,  700, 17000),
     ("huge_docs_few_topics", 4,   50,   24,  16500),
-    # rows of more than 768 entries: walked twice by a whole wave (4-byte and 6-byte entries)
+    # rows too long for the kept pass shapes: walked twice by a whole wave (4-byte and 2-byte entries)
     ("rows_over_768",        6,   300,  1200, 9000),
     ("rows_over_768_split",  3,   300,  1100, 17500),
+    ("rows_near_k_tiny",     3,   300,  1023, 30000),     # the largest K of the 2-byte entries
+    ("k_first_packed",       30,  300,  1024, 400),       # the smallest K of the 4-byte entries
 ]
 
 
@@ -135,6 +138,39 @@ def test_edge_shapes(mlda, case):
     z = oracle.init_topics(c.T, K, SEED)
     assert np.array_equal(model.assignments(), z)
     for it in (1, 2, 3):
+        z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
+    model.close()
+
+
+@pytest.mark.parametrize("K", [500, 1500])
+def test_counts_beyond_one_entry(mlda, K):
+    """Documents whose tokens sit in one or two topics: counts of 20,000 to 70,000, which no entry
+    of a theta row holds (15 with 2-byte entries, K = 500; 16,383 with 4-byte entries, K = 1500),
+    so that a topic takes several entries in a row, also across the lanes of the row walk; a
+    document of 2^16 tokens or more needs 32-bit counters in the rebuild."""
+    V = 60
+    lens = np.array([70000, 40000, 20000, 300, 17, 1, 16384, 15, 16], dtype=np.int64)
+    doc_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rng = np.random.default_rng(K)
+    words = rng.integers(V, size=int(lens.sum())).astype(np.int32)
+    z = rng.integers(K, size=len(words)).astype(np.uint16)
+    z[doc_ptr[0]:doc_ptr[1]] = 3                                   # one topic
+    z[doc_ptr[1]:doc_ptr[1] + 20000] = 0                           # two topics, at both ends of a row
+    z[doc_ptr[1] + 20000:doc_ptr[2]] = K - 1
+    z[doc_ptr[2]:doc_ptr[3]] = rng.integers(5, size=20000) * 7     # five topics
+    z[doc_ptr[6]:doc_ptr[7]] = 11                                  # exactly 2^14 tokens of one topic
+    z[doc_ptr[7]:doc_ptr[8]] = 2                                   # exactly 15
+    z[doc_ptr[8]:doc_ptr[9]] = 2                                   # exactly 16
+
+    class C:  # minimal corpus record
+        pass
+    c = C(); c.doc_ptr = doc_ptr; c.word_ids = words; c.T = len(words)
+    alpha, beta = 50.0 / K, 0.01
+    model = mlda.Mlda(doc_ptr, words, V, K, alpha, beta, SEED)
+    model.set_assignments(z, it=0)
+    assert np.array_equal(model.assignments(), z)
+    check_counts(model, c, z, V, K)
+    for it in (1, 2):
         z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
     model.close()
 
@@ -161,7 +197,7 @@ def test_mixed_row_lengths(mlda):
     model.init_random()
     z = oracle.init_topics(c.T, K, SEED)
     nnz = np.diff(model.doc_topic_csr()[0])
-    assert nnz.min() <= 16 and nnz.max() > 768      # from the narrowest shape to the long walk
+    assert nnz.min() <= 16 and nnz.max() > 768      # from the narrowest shape to the widest
     for it in (1, 2, 3):
         z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
     model.close()
@@ -219,7 +255,7 @@ def test_streamed_chunks_match_oracle(mlda, chunks):
 
 
 def test_streamed_edge_cases(mlda):
-    """More chunks than documents, empty documents, long rows in 6-byte entries, and a saved
+    """More chunks than documents, empty documents, long documents over few topics, and a saved
     state carried from a resident context into a streamed one."""
     base = corpus_synth.tiny(D=5, V=30, K=9, mean_len=12, seed=3)
     lens = np.diff(base.doc_ptr)
@@ -238,7 +274,7 @@ def test_streamed_edge_cases(mlda):
         z = check_step(model, c, z, V, K, alpha, beta, 11, it)
     model.close()
 
-    big = corpus_synth.tiny(D=4, V=40, K=50, mean_len=16500, seed=8)      # 6-byte theta entries
+    big = corpus_synth.tiny(D=4, V=40, K=50, mean_len=16500, seed=8)      # counts spread over many entries
     model = mlda.Mlda(big.doc_ptr, big.word_ids, 40, 50, 1.0, 0.01, SEED, chunks=3)
     model.init_random()
     z = oracle.init_topics(big.T, 50, SEED)
@@ -353,15 +389,22 @@ def test_step_with_loglik_flag_and_timing(mlda):
     n_tiles = int(np.ceil(per_word / 1024).sum())
     n_wide_tiles = int(np.ceil(per_word[per_word >= 2**16] / 1024).sum())   # int32 rows of phi
     lens = np.diff(c.doc_ptr)
-    before = oracle.doc_topic_csr(c.doc_ptr, model.assignments(), cfg.K)[0]
+
+    def row_entries(assignments):
+        """Entries of every theta row: K < 1024 gives 2-byte entries that hold counts up to 15,
+        so a larger count takes several."""
+        row_ptr, _, counts = oracle.doc_topic_csr(c.doc_ptr, assignments, cfg.K)
+        per_topic = -(-counts.astype(np.int64) // 15)
+        return np.array([per_topic[row_ptr[d]:row_ptr[d + 1]].sum() for d in range(len(lens))])
+
+    assert cfg.K < 1024
+    before = row_entries(model.assignments())
     model.step(2)
-    mid = oracle.doc_topic_csr(c.doc_ptr,
-                               oracle.iteration(c.doc_ptr, c.word_ids, z, cfg.V, cfg.K, cfg.alpha,
-                                                cfg.beta, SEED, 5), cfg.K)[0]
+    mid = row_entries(oracle.iteration(c.doc_ptr, c.word_ids, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, SEED, 5))
     got = model.sampler_bytes()
-    for row_ptr, b in zip((before, mid), got):
-        entry_bytes = 4.0 if lens.max() < 2**14 else 6.0       # packed theta entries when counts fit 14 bits
-        want = (16.0 * c.T + entry_bytes * float((lens * np.diff(row_ptr)).sum())
+    assert (before > np.diff(oracle.doc_topic_csr(c.doc_ptr, z, cfg.K)[0])).any()     # some counts are spread
+    for entries, b in zip((before, mid), got):
+        want = (16.0 * c.T + 2.0 * float((lens * entries).sum())
                 + cfg.K * (2.0 * n_tiles + 2.0 * n_wide_tiles))
         assert b == want
     assert len(got) == 2
