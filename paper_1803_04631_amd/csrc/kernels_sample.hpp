@@ -111,11 +111,17 @@ template <int kGroup>
 __device__ __forceinline__ int dense_bucket_search(const float* pstar, const double* cp, int K,
                                                    int ng, double alpha, double y, int o,
                                                    float w_o, double delta) {
-    int lo = 0, hi = ng;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        const double pre = cp[mid] + ((mid * kGroup + (kGroup - 1) >= o) ? delta : 0.0);
-        if (alpha * pre > y) hi = mid; else lo = mid + 1;
+    // Bisection with steps of falling powers of two: `lo` counts the groups known to lie
+    // before the draw.  Every lane makes the same number of steps, so the scalar unit runs the
+    // loop, and a step is one LDS read, the correction and one comparison.
+    const int o_group = o / kGroup;        // groups from here on hold the own topic's correction
+    int lo = 0;
+    for (int step = 1 << (31 - __builtin_clz(ng)); step > 0; step >>= 1) {
+        const int upto = lo + step;        // would groups 0 .. upto - 1 all lie before the draw?
+        if (upto <= ng) {
+            const double pre = cp[upto - 1] + (upto > o_group ? delta : 0.0);
+            if (!(alpha * pre > y)) lo = upto;
+        }
     }
     if (lo >= ng) return K - 1;
     const int k0 = lo * kGroup;
