@@ -177,24 +177,6 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    if args.chunks > 1:
-        # chunks take turns on the GPU: no per-kernel times, the rate includes the transfers
-        value = T * args.steps / elapsed
-        log("streamed in %d chunks: %.2f ms per iteration, %.4g tokens/s (PCIe-inclusive)"
-            % (args.chunks, elapsed / args.steps * 1e3, value))
-        print(json.dumps({
-            "metric": "sampled tokens/sec per iteration (1 GPU, corpus streamed over PCIe)",
-            "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-            "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-            "config": {"workload": "%s: D=%d V=%d K=%d T=%d, alpha=50/K, beta=0.01, streamed in %d chunks"
-                                   % (cfg.name, cfg.D, cfg.V, cfg.K, T, args.chunks),
-                       "step": "per chunk: upload, rebuild theta, sample, add to phi, rebuild theta "
-                               "for the log-likelihood, download; then n_k and the log-likelihood",
-                       "loglik_per_token": model.loglik() / T},
-            "roofline": None}), flush=True)
-        model.close()
-        return
     ms = model.timing()                       # [steps, 4] HIP-event times on the library's stream
     algo_bytes = model.sampler_bytes()        # [steps] algorithmic bytes of each sampling launch
     ll = model.loglik()
@@ -202,7 +184,7 @@ def main():
     mean_ms = ms.mean(axis=0)
     sample_ms = float(mean_ms[0])
     achieved = float((algo_bytes / (ms[:, 0] * 1e-3)).mean()) / 1e9      # GB/s, per launch then mean
-    measured = MEASURED_TRAFFIC_KIB.get((cfg.name, args.state))
+    measured = MEASURED_TRAFFIC_KIB.get((cfg.name, args.state)) if args.chunks == 1 else None
     traffic = traffic_source = hbm_gbs = None
     if measured:
         traffic = (measured[0] * FETCH_SCALE + measured[1] * WRITE_SCALE) * 1024.0
@@ -214,8 +196,9 @@ def main():
     log("tokens/s %.4g; sampler %.1f GB/s algorithmic (%.1f%% of %.0f); LL/token %.4f; theta nnz/doc %.1f"
         % (value, achieved, 100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS, ll / T, nnz / cfg.D))
 
+    streamed = args.chunks > 1
     out = {
-        "metric": "sampled tokens/sec per iteration (1 GPU)",
+        "metric": "sampled tokens/sec per iteration (1 GPU)" + (", corpus streamed over PCIe" if streamed else ""),
         "value": value,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -228,11 +211,17 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {
-            "workload": "%s: D=%d V=%d K=%d T=%d, alpha=50/K, beta=0.01, %s start, iterations %d..%d"
+            "workload": "%s: D=%d V=%d K=%d T=%d, alpha=50/K, beta=0.01, %s start, iterations %d..%d%s"
                         % (cfg.name, cfg.D, cfg.V, cfg.K, T,
                            "random-topic" if args.state == "init" else "generated-topic",
-                           args.warmup + 1, args.warmup + args.steps),
-            "step": "sample + rebuild phi/n_k + rebuild theta + log-likelihood",
+                           args.warmup + 1, args.warmup + args.steps,
+                           ", streamed through the GPU in %d chunks (the rate includes the PCIe transfers)"
+                           % args.chunks if streamed else ""),
+            "step": ("per chunk: upload, topics to word-major order, rebuild theta, sample, add to phi, "
+                     "topics back to document order, rebuild theta for the log-likelihood, download; then "
+                     "n_k and the log-likelihood; kernel times are sums over the chunks (ms_rebuild_theta "
+                     "includes the two order changes)") if streamed
+                    else "sample + rebuild phi/n_k + rebuild theta + log-likelihood",
             "ms_sample": sample_ms, "ms_rebuild_phi": float(mean_ms[1]),
             "ms_rebuild_theta": float(mean_ms[2]), "ms_loglik": float(mean_ms[3]),
             "tokens_per_s_without_loglik": T / (float(mean_ms[:3].sum()) * 1e-3),
@@ -243,7 +232,7 @@ def main():
             "paper_context": PAPER_CONTEXT.get(cfg.name),
         },
         "roofline": {
-            "kernel": "sample_kernel",
+            "kernel": "sample_kernel" + (" (sum over the chunks of an iteration)" if streamed else ""),
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,

@@ -96,8 +96,11 @@ int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
  * of an iteration are frozen and the uniforms are keyed by the caller's token index.
  * The workspace (mlda_workspace_bytes_streamed: two copies of phi and two chunk buffers) and
  * the other arguments are as for mlda_create; doc_ptr is read by the sizing call too.
- * Differences in use: mlda_get_timing and mlda_get_sampler_bytes report no rows; the theta
- * getters and mlda_get_loglik (when the last step did not evaluate it) revisit every chunk.
+ * Differences in use: the rows of mlda_get_timing and mlda_get_sampler_bytes are sums over the
+ * chunk visits of an iteration (kernel time on the context's stream: waiting for a transfer is
+ * not in them), and the third column of mlda_get_timing also holds the two changes of token
+ * order a visit needs; the theta getters and mlda_get_loglik (when the last step did not
+ * evaluate it) revisit every chunk.
  */
 int mlda_workspace_bytes_streamed(const int64_t* doc_ptr, int64_t D, int32_t V, int32_t K,
                                   int32_t n_chunks, size_t* bytes);

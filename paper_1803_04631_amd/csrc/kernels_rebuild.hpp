@@ -539,34 +539,28 @@ __global__ __launch_bounds__(kWave) void derive_tok_slot_kernel(const DocRec* do
     }
 }
 
-// The same without the map, in two steps.  First the document of every 64th token of the
-// chunk is found by bisection of the chunk's doc_ptr (D + 1 entries, tokens numbered from 0
-// inside the chunk): block_doc[b] = the last d with doc_ptr[d] <= 64 b.
-__global__ void derive_block_doc_kernel(const int32_t* doc_ptr, int32_t D, int64_t n_blocks,
-                                        int32_t* block_doc) {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= n_blocks) return;
-    const int32_t t = (int32_t)(b * 64);
-    int lo = 0, hi = D;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (doc_ptr[mid] <= t) lo = mid; else hi = mid;
+// A chunk without a map (its assignments arrive in document order): every token's topic is
+// paired with the slot of its document's theta row, one wave per document, persistent, where
+// both are contiguous ...
+__global__ __launch_bounds__(kWave) void pair_topics_with_slots_kernel(const DocRec* docs, int64_t D,
+                                                                       const uint16_t* z_doc, uint2* pairs) {
+    const int lane = (int)threadIdx.x;
+    for (int64_t i = blockIdx.x; i < D; i += gridDim.x) {
+        const DocRec r = docs[i];
+        for (int j = lane; j < r.n; j += kWave)
+            pairs[r.begin + j] = make_uint2(r.slot, (uint32_t)z_doc[r.begin + j]);
     }
-    block_doc[b] = lo;
 }
 
-// Then every word-major token starts at its block's document and walks forward to its own
-// (at most a few documents, unless they are very short).
-__global__ void derive_tok_slot_by_search_kernel(const int32_t* tok_id, int64_t T, int64_t first,
-                                                 const int32_t* doc_ptr, int32_t D,
-                                                 const int32_t* block_doc, const uint2* row_rec,
-                                                 uint32_t* tok_slot) {
+// ... and one gather per word-major token brings both along (tok_id counts from the start of
+// the whole corpus, the pairs from token `first`).
+__global__ void pairs_to_word_major_kernel(const uint2* pairs, const int32_t* tok_id, uint16_t* z_word,
+                                           uint32_t* tok_slot, int64_t T, int64_t first) {
     const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (pos >= T) return;
-    const int32_t t = (int32_t)((int64_t)tok_id[pos] - first);
-    int d = block_doc[t >> 6];
-    while (d + 1 < D && doc_ptr[d + 1] <= t) ++d;
-    tok_slot[pos] = row_rec[d].x;
+    const uint2 p = pairs[(int64_t)tok_id[pos] - first];
+    tok_slot[pos] = p.x;
+    z_word[pos] = (uint16_t)p.y;
 }
 
 // Boundary order changes.  doc_map[t] = word-major position of document-major token t;

@@ -73,6 +73,11 @@ const void* theta_kernel_for(bool tiny, bool wide_counters) {
                          : (const void*)mlda::theta_rows_kernel<mlda::PackedRows, false>;
 }
 constexpr int kMaxTimedIters = 1024;
+// events of a streamed chunk visit: its uploads have arrived | topics and slots in word-major
+// order | theta rebuilt | sampled | phi added to | new topics in document order | theta of the
+// new topics (log-likelihood)
+constexpr int kVisitEvents = 7;
+constexpr int kMaxTimedVisits = 4096;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -98,11 +103,14 @@ constexpr int kEntryRing = 2048;      // per-rebuild counters of theta row entri
 // rows follow.
 struct ChunkLayout {
     size_t tok_slot = 0, tok_id = 0, doc_map = 0, doc_ptr = 0, doc_order = 0, row_rec = 0, tiles = 0,
-           segs = 0, split = 0, static_bytes = 0, block_doc = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
+           segs = 0, split = 0, static_bytes = 0, doc_pairs = 0, z0 = 0, z1 = 0, slots = 0, total = 0;
 };
 
+// `streamed`: the chunk takes turns on the device with others.  It then needs no
+// document->token map: its assignments arrive in document order (z_doc, in the map's place) and
+// are paired with their documents' slots there (doc_pairs) on their way to word-major order.
 ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tiles, size_t n_segs,
-                         size_t n_split) {
+                         size_t n_split, bool streamed) {
     ChunkLayout L;
     size_t at = 0;
     auto put = [&](size_t bytes) { const size_t o = at; at += align_up(bytes, kAlign); return o; };
@@ -115,8 +123,8 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
     L.split = put(n_split * 4);
     L.static_bytes = at;
     L.tok_slot = put((size_t)T * 4);       // derived on the device from the static part
-    L.doc_map = put((size_t)T * 4);
-    L.block_doc = put(((size_t)T / 64 + 1) * 4);
+    L.doc_map = put((size_t)T * (streamed ? 2 : 4));
+    L.doc_pairs = put(streamed ? (size_t)T * 8 : 0);
     L.z0 = put((size_t)T * 2);
     L.z1 = put((size_t)T * 2);
     L.slots = put(slots_bytes);
@@ -125,13 +133,13 @@ ChunkLayout chunk_layout(int64_t D, int64_t T, size_t slots_bytes, size_t n_tile
 }
 
 // An upper bound of the same from the sizes alone.
-ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K) {
+ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K, bool streamed) {
     const size_t tile = (size_t)tile_tokens_for(K);
     // (at most one entry of at most 4 bytes per token, a header, a unit's and a slot's rounding)
     const size_t slots = kSlotAlign + (size_t)T * 4 + (size_t)D * (mlda::kRowHeader + 16 + kSlotAlign);
     const size_t n_tiles = (size_t)T / tile + (size_t)V + 1;
     const size_t n_segs = (size_t)T / kPhiSegment + (size_t)V + 1;
-    return chunk_layout(D, T, slots, n_tiles, n_segs, (size_t)V);
+    return chunk_layout(D, T, slots, n_tiles, n_segs, (size_t)V, streamed);
 }
 
 // The model and the scratch of the reductions.
@@ -316,7 +324,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         if (!accumulate && n > kPhiSegment) ++n_split;
     }
     h.n_tiles = (int32_t)n_tiles; h.n_segs = (int32_t)n_segs; h.n_split = (int32_t)n_split;
-    h.L = chunk_layout(D, T, h.slots_bytes, n_tiles, n_segs, n_split);
+    h.L = chunk_layout(D, T, h.slots_bytes, n_tiles, n_segs, n_split, accumulate);
 
     h.release();
     h.pinned = pinned;
@@ -440,8 +448,17 @@ struct mlda_ctx {
     int64_t rebuilds = 0;                        // rebuilds launched so far
     int32_t last_step_iters = 0;
     bool has_state = false, ll_fresh = false;
-    std::vector<hipEvent_t> events;     // 5 per timed iteration
+    std::vector<hipEvent_t> events;     // 5 per timed iteration (streamed: kVisitEvents per timed visit)
     int32_t timed_iters = 0;            // iterations of the last step that carry events
+    // streamed: what mlda_get_timing and mlda_get_sampler_bytes need of every timed chunk visit
+    struct Visit {
+        int32_t iter_row;               // row of the step's timed iterations
+        int64_t T;
+        int32_t n_tiles, n_wide_tiles;
+        int64_t rebuild;                // number of the theta rebuild the visit's sampling read
+        size_t event0;                  // first of its kVisitEvents events
+    };
+    std::vector<Visit> visit_log;
 
     // ---- the chunks (one: attached for good; several: attached in turn, Algorithm 1 WorkSchedule2)
     std::vector<HostChunk> chunks;
@@ -459,7 +476,8 @@ struct mlda_ctx {
     const HostChunk* at = nullptr;
     int64_t D = 0, T = 0;
     uint32_t* tok_slot = nullptr;        // [T] slot of the theta row of each word-major token's document
-    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr, *block_doc = nullptr;
+    int32_t *tok_id = nullptr, *doc_map = nullptr, *doc_ptr = nullptr;
+    uint2* doc_pairs = nullptr;          // streamed: {slot of the token's document, its topic}, document order
     mlda::DocRec* doc_order = nullptr;   // documents by falling length, as the theta rebuild walks them
     int32_t theta_grid = 0;
     bool tiny = false, wide_counters = false, short_docs = true;
@@ -537,7 +555,7 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
     c->tok_id = (int32_t*)(base + h.L.tok_id);
     c->doc_map = (int32_t*)(base + h.L.doc_map);
-    c->block_doc = (int32_t*)(base + h.L.block_doc);
+    c->doc_pairs = (uint2*)(base + h.L.doc_pairs);
     c->z_doc = (uint16_t*)(base + h.L.doc_map);   // a streamed chunk needs no map, see derive_chunk_arrays
     c->doc_ptr = (int32_t*)(base + h.L.doc_ptr);
     c->doc_order = (mlda::DocRec*)(base + h.L.doc_order);
@@ -563,13 +581,8 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
 // and hands them back so: its theta rebuilds read them directly and it needs no map (building
 // one costs as much as a theta rebuild); the tokens' slots are then found by bisection.
 void derive_chunk_arrays(mlda_ctx* c) {
-    if (c->T > 0 && c->streamed) {
-        const int64_t n_blocks = c->T / 64 + 1;
-        hipLaunchKernelGGL(mlda::derive_block_doc_kernel, dim3(blocks_for(n_blocks, 256)), dim3(256), 0,
-                           c->stream, c->doc_ptr, (int32_t)c->D, n_blocks, c->block_doc);
-        hipLaunchKernelGGL(mlda::derive_tok_slot_by_search_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0,
-                           c->stream, c->tok_id, c->T, c->at->tok_begin, c->doc_ptr, (int32_t)c->D,
-                           c->block_doc, c->row_rec, c->tok_slot);
+    if (c->streamed) {
+        // (the slots of a streamed chunk's tokens come with its assignments, see attach)
     } else if (c->T > 0) {
         hipLaunchKernelGGL(mlda::derive_doc_map_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
                            c->tok_id, c->T, c->at->tok_begin, c->doc_map);
@@ -587,7 +600,7 @@ void derive_chunk_arrays(mlda_ctx* c) {
 // chunk's assignments, caller's order, into z_doc) is copied on the copy stream, so that it
 // overlaps the kernels of the chunk before; the context's stream then waits for it and, with_z,
 // also puts the assignments in word-major order into z[0].
-int attach(mlda_ctx* c, int32_t m, bool with_z) {
+int attach(mlda_ctx* c, int32_t m, bool with_z, hipEvent_t* ev = nullptr) {
     const HostChunk& h = c->chunks[(size_t)m];
     const int s = (int)(c->visits % 2);
     c->visits += 1;
@@ -604,10 +617,18 @@ int attach(mlda_ctx* c, int32_t m, bool with_z) {
     }
     HIP_TRY(hipEventRecord(c->slot_ready[s], c->copy_stream));
     HIP_TRY(hipStreamWaitEvent(c->stream, c->slot_ready[s], 0));
+    if (ev) HIP_TRY(hipEventRecord(ev[0], c->stream));
     derive_chunk_arrays(c);
-    if (with_z && h.T > 0)
-        hipLaunchKernelGGL(mlda::to_word_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0, c->stream,
-                           c->z_doc, c->tok_id, c->z[0], h.T, h.tok_begin);
+    if (with_z && h.T > 0) {
+        // every token's topic is paired with the slot of its document's theta row where both
+        // are contiguous, and the pairs are then brought to word-major order in one gather
+        const int grid = (int)std::min<int64_t>(h.D, (int64_t)c->n_cus * 32);
+        hipLaunchKernelGGL(mlda::pair_topics_with_slots_kernel, dim3((unsigned)grid), dim3(mlda::kWave), 0,
+                           c->stream, c->doc_order, h.D, c->z_doc, c->doc_pairs);
+        hipLaunchKernelGGL(mlda::pairs_to_word_major_kernel, dim3(blocks_for(h.T, 256)), dim3(256), 0,
+                           c->stream, c->doc_pairs, c->tok_id, c->z[0], c->tok_slot, h.T, h.tok_begin);
+    }
+    if (ev) HIP_TRY(hipEventRecord(ev[1], c->stream));
     return launch_check("attaching a chunk");
 }
 
@@ -834,7 +855,7 @@ size_t streamed_workspace_bound(const int64_t* doc_ptr, int64_t D, int32_t V, in
     size_t chunk = 0;
     for (int32_t m = 0; m < M; ++m) {
         const int64_t a = chunk_first(doc_ptr, D, M, m), b = chunk_first(doc_ptr, D, M, m + 1);
-        chunk = std::max(chunk, chunk_layout_bound(b - a, doc_ptr[b] - doc_ptr[a], V, K).total);
+        chunk = std::max(chunk, chunk_layout_bound(b - a, doc_ptr[b] - doc_ptr[a], V, K, true).total);
     }
     return model_layout(V, K, doc_ptr[D], true).total + 2 * chunk;
 }
@@ -1080,7 +1101,7 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
     if (!bytes) return fail(MLDA_EINVAL, "bytes is null");
     if (D < 0 || T < 0 || V < 1 || K < 1 || K > 65535 || T >= ((int64_t)1 << 31))
         return fail(MLDA_EINVAL, "need D >= 0, 0 <= T < 2^31, V >= 1, 1 <= K <= 65535");
-    *bytes = model_layout(V, K, T, false).total + chunk_layout_bound(D, T, V, K).total;
+    *bytes = model_layout(V, K, T, false).total + chunk_layout_bound(D, T, V, K, false).total;
     return MLDA_OK;
 }
 
@@ -1298,22 +1319,43 @@ int mlda_set_assignments(mlda_ctx* c, const uint16_t* z, int32_t iter) {
 
 // One iteration with several chunks (Algorithm 1, WorkSchedule2; Section 4: every chunk
 // samples against the phi of the iteration's start, the new phi is the sum over chunks).
-static int step_streamed(mlda_ctx* c, bool loglik) {
+static int step_streamed(mlda_ctx* c, bool loglik, int32_t timed_row) {
     const int next = c->model_cur ^ 1;
     RC_TRY(begin_model(c, next));
     bool first = true;
     for (int32_t m = 0; m < (int32_t)c->chunks.size(); ++m) {
         if (c->chunks[(size_t)m].D == 0) continue;
-        RC_TRY(attach(c, m, true));
+        hipEvent_t* ev = nullptr;
+        if (timed_row >= 0 && (int)c->visit_log.size() < kMaxTimedVisits) {
+            const size_t event0 = c->visit_log.size() * kVisitEvents;
+            while (c->events.size() < event0 + kVisitEvents) {
+                hipEvent_t e;
+                HIP_TRY(hipEventCreate(&e));
+                c->events.push_back(e);
+            }
+            ev = &c->events[event0];
+        }
+        RC_TRY(attach(c, m, true, ev));
+        if (ev) {
+            try {
+                c->visit_log.push_back({timed_row, c->T, c->n_tiles, c->n_wide_tiles, c->rebuilds,
+                                        (size_t)(ev - c->events.data())});
+            } catch (const std::bad_alloc&) { return fail(MLDA_ENOMEM, "out of host memory"); }
+        }
         RC_TRY(rebuild_theta(c, c->z_doc));            // theta is not kept between visits
+        if (ev) HIP_TRY(hipEventRecord(ev[2], c->stream));
         RC_TRY(launch_sampler(c, c->z[0], c->z[1]));
+        if (ev) HIP_TRY(hipEventRecord(ev[3], c->stream));
         RC_TRY(rebuild_phi(c, c->z[1], next));
+        if (ev) HIP_TRY(hipEventRecord(ev[4], c->stream));
         RC_TRY(to_document_order(c, c->z[1]));
+        if (ev) HIP_TRY(hipEventRecord(ev[5], c->stream));
         if (loglik) {
             RC_TRY(rebuild_theta(c, c->z_doc));
             RC_TRY(add_theta_loglik(c, first));
             first = false;
         }
+        if (ev) HIP_TRY(hipEventRecord(ev[6], c->stream));
         RC_TRY(store_z_and_release(c, m, true));
     }
     RC_TRY(finish_model(c, next));
@@ -1335,9 +1377,17 @@ int mlda_step(mlda_ctx* c, int32_t n_iters, uint32_t flags) {
     RC_TRY(need_state(c));
     if (n_iters < 0) return fail(MLDA_EINVAL, "n_iters must be >= 0");
     if (c->streamed) {
-        c->timed_iters = 0;
-        c->last_step_iters = 0;
-        for (int32_t i = 0; i < n_iters; ++i) RC_TRY(step_streamed(c, (flags & MLDA_STEP_LOGLIK) != 0));
+        // the last iterations of the step are timed, as many as the visit log holds
+        int32_t visits_per_iter = 0;
+        for (const HostChunk& h : c->chunks) visits_per_iter += h.D > 0 ? 1 : 0;
+        const int32_t timed = visits_per_iter == 0 ? 0
+            : std::min({n_iters, kMaxTimedIters, kMaxTimedVisits / visits_per_iter,
+                        kEntryRing / (2 * visits_per_iter) - 1});
+        c->visit_log.clear();
+        c->timed_iters = std::max(timed, 0);
+        c->last_step_iters = n_iters;
+        for (int32_t i = 0; i < n_iters; ++i)
+            RC_TRY(step_streamed(c, (flags & MLDA_STEP_LOGLIK) != 0, i - (n_iters - c->timed_iters)));
         return MLDA_OK;
     }
     const int32_t timed = std::min(n_iters, kMaxTimedIters);
@@ -1486,6 +1536,25 @@ int mlda_get_timing(mlda_ctx* c, double* ms, int32_t capacity_iters, int32_t* n_
     HIP_TRY(hipStreamSynchronize(c->stream));
     const int32_t n = std::min(c->timed_iters, capacity_iters);
     const int32_t first = c->timed_iters - n;
+    if (c->streamed) {
+        // per iteration the sums over its chunk visits: sampling | phi | theta rebuild and the
+        // two order changes | the theta rebuild of the new topics (log-likelihood)
+        HIP_TRY(hipStreamSynchronize(c->down_stream));
+        for (int32_t i = 0; i < 4 * n; ++i) ms[i] = 0.0;
+        for (const mlda_ctx::Visit& v : c->visit_log) {
+            if (v.iter_row < first) continue;
+            hipEvent_t* ev = &c->events[v.event0];
+            float t[kVisitEvents - 1];
+            for (int j = 0; j + 1 < kVisitEvents; ++j) HIP_TRY(hipEventElapsedTime(&t[j], ev[j], ev[j + 1]));
+            double* row = ms + (size_t)(v.iter_row - first) * 4;
+            row[0] += t[2];
+            row[1] += t[3];
+            row[2] += t[0] + t[1] + t[4];
+            row[3] += t[5];
+        }
+        *n_iters = n;
+        return MLDA_OK;
+    }
     for (int32_t i = 0; i < n; ++i) {
         hipEvent_t* ev = &c->events[(size_t)(first + i) * 5];
         for (int j = 0; j < 4; ++j) {
@@ -1508,13 +1577,26 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
     HIP_TRY(hipMemcpyAsync(ring.data(), c->row_entries, (size_t)kEntryRing * 8, hipMemcpyDeviceToHost,
                            c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
+    const double entry_bytes = tiny_rows_for(c->K) ? 2.0 : 4.0;
+    if (c->streamed) {          // per iteration the sum over its chunk visits
+        const int32_t m = std::min(c->timed_iters, capacity_iters), first = c->timed_iters - m;
+        for (int32_t i = 0; i < m; ++i) bytes[i] = 0.0;
+        for (const mlda_ctx::Visit& v : c->visit_log) {
+            if (v.iter_row < first) continue;
+            bytes[v.iter_row - first] += 16.0 * (double)v.T +
+                entry_bytes * (double)ring[(size_t)(v.rebuild % kEntryRing)] +
+                (double)c->K * (2.0 * (double)v.n_tiles + 2.0 * (double)v.n_wide_tiles);
+        }
+        *n_iters = m;
+        return MLDA_OK;
+    }
     for (int32_t i = 0; i < n; ++i) {
         const int32_t j = c->last_step_iters - n + i;
         const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
         // per token: row slot 4, token id 4, old topic 2, new topic 2, row length 4
         // per tile: the word's row of phi, 2 K bytes, or 4 K for a word with 2^16 tokens or more
-        bytes[i] = 16.0 * (double)c->T + (c->tiny ? 2.0 : 4.0) * row_entries +
+        bytes[i] = 16.0 * (double)c->T + entry_bytes * row_entries +
                    (double)c->K * (2.0 * (double)c->n_tiles + 2.0 * (double)c->n_wide_tiles);
     }
     *n_iters = n;

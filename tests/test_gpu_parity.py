@@ -250,7 +250,9 @@ def test_streamed_chunks_match_oracle(mlda, chunks):
     n_wk, n_k = check_counts(model, c, z, cfg.V, cfg.K)
     ll = oracle.loglik(c.doc_ptr, z, cfg.V, cfg.K, cfg.alpha, cfg.beta, n_wk, n_k)
     assert abs(model.loglik() - ll) <= LL_RTOL * abs(ll)
-    assert len(model.timing()) == 0           # per-kernel times are not kept for streamed chunks
+    ms, moved = model.timing(), model.sampler_bytes()      # per iteration, summed over the chunks
+    assert ms.shape == (2, 4) and np.all(ms > 0) and moved.shape == (2,)
+    assert np.all(moved >= 16.0 * c.T)
     model.close()
 
 
