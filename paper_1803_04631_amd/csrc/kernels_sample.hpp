@@ -416,7 +416,8 @@ __device__ __forceinline__ void row_pass_searched(TokenRec* rec, int sl, const u
 #pragma unroll
     for (int i = n - 2; i >= 0; --i)
         if (sums[i] > d.y) entry = Layout::word(raw[i / UE], i % UE);
-    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no sum above the draw:
+    if (__builtin_expect(__ballot(d.hit && !(acc > d.y)) != 0, 0)) {   // rounding left no sum above the draw:
+        asm volatile("");                            // (a branch of its own: it is almost never taken)
         if (d.hit && !(acc > d.y)) {                 // take the lane's last entry with weight
             double before = 0.0;
 #pragma unroll
@@ -458,7 +459,8 @@ __device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, int first_u
 #pragma unroll
     for (int c = kUnits - 2; c >= 0; --c)
         if (at_end[c] > d.y) unit = c;
-    if (__ballot(d.hit && !(acc > d.y)) != 0) {      // rounding left no sum above the draw:
+    if (__builtin_expect(__ballot(d.hit && !(acc > d.y)) != 0, 0)) {   // rounding left no sum above the draw:
+        asm volatile("");                            // (a branch of its own: it is almost never taken)
         if (d.hit && !(acc > d.y)) {                 // take the lane's last unit with weight
             double before_unit = 0.0;
 #pragma unroll
