@@ -28,10 +28,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # this chip, WRITE_SIZE by 1.000 (same summaries).
 FETCH_SCALE, WRITE_SCALE = 2.000, 1.000
 MEASURED_TRAFFIC_KIB = {
-    ("C4", "init"): (1.17496e8, 2.4738e6, "profiles/sample_kernel_C4.md"),
-    ("C3", "init"): (2.0689e7, 3.70e5, "profiles/sample_kernel_C3_C5.md"),
-    ("C5", "init"): (2.8363e7, 1.347e6, "profiles/sample_kernel_C3_C5.md"),
+    ("C4", "init"): (7.32182e7, 1.63922e6, "profiles/sample_kernel_C4.md"),
+    ("C3", "init"): (1.2373e7, 2.24057e5, "profiles/sample_kernel_C3_C5.md"),
+    ("C5", "init"): (2.77971e7, 2.24608e5, "profiles/sample_kernel_C3_C5.md"),
 }
+# VALU wave-instructions per sampling launch (SQ_INSTS_VALU, same summaries): the sampler's other
+# limit is instruction issue, 1024 SIMDs x 2.4 GHz / 4 cycles per wave-instruction
+MEASURED_VALU_INSTS = {("C4", "init"): 1.7585e10, ("C3", "init"): 4.428e9, ("C5", "init"): 7.126e9}
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4.0
 
 
 # The paper's own single-GPU rates (its Table 4, mean of the first 100 iterations) on the
@@ -185,6 +189,7 @@ def main():
     sample_ms = float(mean_ms[0])
     achieved = float((algo_bytes / (ms[:, 0] * 1e-3)).mean()) / 1e9      # GB/s, per launch then mean
     measured = MEASURED_TRAFFIC_KIB.get((cfg.name, args.state)) if args.chunks == 1 else None
+    valu_insts = MEASURED_VALU_INSTS.get((cfg.name, args.state)) if args.chunks == 1 else None
     traffic = traffic_source = hbm_gbs = None
     if measured:
         traffic = (measured[0] * FETCH_SCALE + measured[1] * WRITE_SCALE) * 1024.0
@@ -250,6 +255,10 @@ def main():
             "hbm_gbs": hbm_gbs,
             "hbm_frac": hbm_gbs / HBM_PEAK_GBS if hbm_gbs else None,
             "traffic_source": traffic_source,
+            # the unit that is busiest: VALU issue (instructions from the same committed profile
+            # over this run's launch time, against the chip's issue rate)
+            "valu_insts_per_launch": valu_insts,
+            "valu_issue_frac": valu_insts / VALU_ISSUE_PEAK / (sample_ms * 1e-3) if valu_insts else None,
         },
     }
     model.close()
