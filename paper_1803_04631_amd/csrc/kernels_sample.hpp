@@ -691,7 +691,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // where a pass's rows are, and the loads of the units its lanes keep.  `rec` is the
         // record of the lane's token, `sl` the lane's place inside its group.  A pass that
         // would run past the batch's 64 records works on the last one several times over.
-        auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, uint4* raw) {
+        auto request = [&](int t0, int shape, TokenRec*& rec, int& sl, uint4* raw, bool live) {
             const int nu = units_of(shape);
             if (shape != geo_shape) {       // the lanes' places change only with the shape
                 const int lg = lanes_log2(shape);
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             // units the lane loads: those of the shape that the row still has from its first on
-            const int n_mine = min((((int)where.y + UE - 1) / UE) - geo_q0, nu);
+            const int n_mine = live ? min((((int)where.y + UE - 1) / UE) - geo_q0, nu) : 0;
 #pragma unroll
             for (int c = 0; c < kKeptUnits; ++c)
                 raw[c] = load_unit(a.slots, where.x, geo_q0 + c, c < n_mine);
@@ -719,10 +719,13 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             const int first_unit = sl * units_of(shape);
             TokenRec* rec = rec_next;
             t_next += kWave >> lanes_log2(shape);
-            if (t_next < n_here) {
-                shape_next = shape_at(t_next);
-                request(t_next, shape_next, rec_next, sl_next, next_raw);
-            }
+            // The request is made whether or not a pass follows (after the batch's last pass
+            // every lane loads the padding unit): the number of loads in flight behind this
+            // pass's own is then the same on every path, and the pass waits for its own rows
+            // only, not for the first of the following pass's as well.
+            const int t_req = min(t_next, kWave - 1);
+            shape_next = shape_at(t_req);
+            request(t_req, shape_next, rec_next, sl_next, next_raw, t_next < n_here);
             switch (shape) {
             case 0: row_pass_kept<Layout, 4, 1>(rec, sl, first_unit, mine_raw, lane); break;
             case 1: row_pass_kept<Layout, 4, 2>(rec, sl, first_unit, mine_raw, lane); break;
@@ -739,7 +742,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             }
         };
         uint4 raw_a[kKeptUnits], raw_b[kKeptUnits];
-        request(0, shape_next, rec_next, sl_next, raw_a);
+        request(0, shape_next, rec_next, sl_next, raw_a, true);
         while (t_next < n_here) {
             pass(raw_a, raw_b);
             if (t_next < n_here) pass(raw_b, raw_a);
