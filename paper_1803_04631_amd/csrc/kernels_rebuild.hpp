@@ -166,6 +166,20 @@ __device__ __forceinline__ int doc_token_position(const int32_t* doc_map, const 
     return doc_map ? doc_map[r.begin + j] : r.begin + j;
 }
 
+// The same as loads that every lane makes, from an address that exists: past the document's
+// end it is the place of the document's last token (of token 0 of the whole array for an empty
+// document).  The loads of a step are then all in flight together and none of them sits
+// behind a branch, where what follows would wait for everything in flight.
+__device__ __forceinline__ int doc_token_position_any(const int32_t* doc_map, const DocRec& r, int j) {
+    const int at = r.n > 0 ? r.begin + min(j, r.n - 1) : 0;
+    return doc_map ? doc_map[at] : at;
+}
+// The topic found at such a position, -1 for a token past the document's end.
+__device__ __forceinline__ int doc_token_topic(const uint16_t* z, int position, const DocRec& r, int j) {
+    const int k = (int)z[position];
+    return j < r.n ? k : -1;
+}
+
 // LDS bytes of the rebuild's dense row: the counters (two 16-bit counters per dword, or one
 // 32-bit counter per topic when some document has 2^16 tokens or more), then one bit per topic
 // that marks the non-zero bins.
@@ -231,12 +245,16 @@ template <class Layout, bool kWide>
 __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                                                            const int32_t* doc_map,
                                                            const uint16_t* z, uint2* row_rec,
-                                                           unsigned char* slots, int64_t D,
+                                                           unsigned char* slots, int64_t D, int64_t T,
                                                            int32_t K, double alpha,
                                                            const double* lg_table,
                                                            unsigned long long* row_entries,
                                                            double* ll_partial) {
     typedef typename Layout::Entry Entry;
+    if (T == 0) {       // no token anywhere: the loads "past a document's end" still need a place that exists
+        doc_map = nullptr;
+        z = reinterpret_cast<const uint16_t*>(docs);
+    }
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
     const int n_counters = kWide ? K : (K + 1) / 2;
@@ -286,38 +304,47 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                     : (int64_t)blockIdx.x;
     // Three loads deep: the topics of this document's first 128 tokens have been gathered, the
     // positions of the next document's tokens read, and the record after that fetched.
-    DocRec cur = i < D ? docs[i] : none;
-    DocRec nxt = i + step < D ? docs[i + step] : none;
-    DocRec after = i + 2 * step < D ? docs[i + 2 * step] : none;
+    auto record = [&](int64_t d) {      // (the load is made for every d, from the last record if need be)
+        const DocRec r = docs[d < D ? d : D - 1];
+        return d < D ? r : none;
+    };
+    DocRec cur = record(i), nxt = record(i + step), after = record(i + 2 * step);
     int k0, k1;
     {
-        const int c0 = doc_token_position(doc_map, cur, lane);
-        const int c1 = doc_token_position(doc_map, cur, lane + kWave);
-        k0 = c0 >= 0 ? (int)z[c0] : -1;
-        k1 = c1 >= 0 ? (int)z[c1] : -1;
+        const int c0 = doc_token_position_any(doc_map, cur, lane);
+        const int c1 = doc_token_position_any(doc_map, cur, lane + kWave);
+        k0 = doc_token_topic(z, c0, cur, lane);
+        k1 = doc_token_topic(z, c1, cur, lane + kWave);
     }
-    int p0 = doc_token_position(doc_map, nxt, lane);
-    int p1 = doc_token_position(doc_map, nxt, lane + kWave);
+    int p0 = doc_token_position_any(doc_map, nxt, lane);
+    int p1 = doc_token_position_any(doc_map, nxt, lane + kWave);
     for (; i < D; i += step) {
         // on their way while this document is counted: the next document's topics, the
         // positions of the one after, the record after that
-        const int n0 = p0 >= 0 ? (int)z[p0] : -1;
-        const int n1 = p1 >= 0 ? (int)z[p1] : -1;
-        const int q0 = doc_token_position(doc_map, after, lane);
-        const int q1 = doc_token_position(doc_map, after, lane + kWave);
-        const DocRec later = i + 3 * step < D ? docs[i + 3 * step] : none;
+        const int n0 = doc_token_topic(z, p0, nxt, lane);
+        const int n1 = doc_token_topic(z, p1, nxt, lane + kWave);
+        const int q0 = doc_token_position_any(doc_map, after, lane);
+        const int q1 = doc_token_position_any(doc_map, after, lane + kWave);
+        const DocRec later = record(i + 3 * step);
 
         bool outgrown = false;
-        if (cur.n > Layout::kMaxCount) {
-            if (k0 >= 0) outgrown |= count_topic(k0);
-            if (k1 >= 0) outgrown |= count_topic(k1);
-            for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
-                outgrown |= count_topic((int)z[doc_token_position(doc_map, cur, j)]);
-        } else {
-            if (k0 >= 0) count_topic_short(k0);
-            if (k1 >= 0) count_topic_short(k1);
-            for (int j = 2 * kWave + lane; j < cur.n; j += kWave)
-                count_topic_short((int)z[doc_token_position(doc_map, cur, j)]);
+        const bool long_doc = cur.n > Layout::kMaxCount;     // (the same for the whole wave)
+        auto count = [&](int k) {
+            if (k < 0) return;
+            if (long_doc) outgrown |= count_topic(k); else count_topic_short(k);
+        };
+        count(k0);
+        count(k1);
+        // the rest of a longer document, four tokens per lane at a time: their positions
+        // first, then their topics, each group of loads in flight together
+        for (int j = 2 * kWave + lane; j - lane < cur.n; j += 4 * kWave) {
+            int at[4], k[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) at[t] = doc_token_position_any(doc_map, cur, j + t * kWave);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) k[t] = doc_token_topic(z, at[t], cur, j + t * kWave);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) count(k[t]);
         }
         __syncthreads();
         unsigned char* head = slots + (size_t)cur.slot * 16u;
@@ -397,7 +424,7 @@ template <class Layout>
 __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* docs,
                                                                 const int32_t* doc_map,
                                                                 const uint16_t* z, uint2* row_rec,
-                                                                unsigned char* slots, int64_t D,
+                                                                unsigned char* slots, int64_t D, int64_t T,
                                                                 int32_t K, double alpha,
                                                                 const double* lg_table,
                                                                 unsigned long long* row_entries,

@@ -732,12 +732,12 @@ int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
         const DocRec* docs = c->doc_order;
         uint2* row_rec = c->row_rec;
         unsigned char* slots = c->slots;
-        int64_t D = c->D;
+        int64_t D = c->D, T = c->T;
         int32_t K = c->K;
         double alpha = c->alpha;
         const double* lg_table = c->lg_table;
         double* ll_partial = c->ll_partial + 2 * kLoglikBlocks;
-        void* args[] = {&docs, &doc_map, &z, &row_rec, &slots, &D, &K, &alpha, &lg_table, &entries, &ll_partial};
+        void* args[] = {&docs, &doc_map, &z, &row_rec, &slots, &D, &T, &K, &alpha, &lg_table, &entries, &ll_partial};
         HIP_TRY(hipLaunchKernel(kernel, dim3((unsigned)c->theta_grid), dim3(kWave), args, lds, c->stream));
     }
     c->rebuilds += 1;
