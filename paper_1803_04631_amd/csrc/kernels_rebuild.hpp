@@ -419,6 +419,10 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
 // working order, so of similar length) make pair p; the topics of the first 128 tokens of each
 // document of the next pair are on their way while the current pair is counted.
 constexpr int kPairMaxK = 1024;
+constexpr int kPairStage = 256;         // entries of a row that are lined up in LDS before they are stored
+__host__ __device__ inline size_t theta_pair_lds_bytes(int32_t K) {
+    return 2 * theta_hist_bytes(K, false) + (size_t)kThetaLgTable * 8 + 2 * (size_t)kPairStage * 4;
+}
 
 template <class Layout>
 __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* docs,
@@ -438,6 +442,8 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds + (size_t)half * one);
     uint32_t* marks = reinterpret_cast<uint32_t*>(lds + (size_t)half * one + theta_counter_bytes(K, false));
     double* table = reinterpret_cast<double*>(lds + 2 * one);
+    // per half: room to line up a row's entries before they are stored
+    Entry* stage = reinterpret_cast<Entry*>(lds + 2 * one + (size_t)kThetaLgTable * 8) + half * kPairStage;
     const double lg_alpha = lg_table[kLgTable];
     for (int k = hl; k < n_counters; k += 32) hist[k] = 0u;
     for (int k = hl; k < n_marks; k += 32) marks[k] = 0u;
@@ -518,22 +524,51 @@ __global__ __launch_bounds__(kWave) void theta_rows_pair_kernel(const DocRec* do
         int at = upto - mine;
         if (w != 0u) marks[hl] = 0u;
         uint32_t pairs = (w | (w >> 1)) & 0x55555555u;
-        while (__ballot(pairs != 0u) != 0) {
-            int lo = 0, hi = 0;
-            if (pairs != 0u) {
-                const int k = hl * 32 + __ffs((int)pairs) - 1;    // even topic of the pair
-                pairs &= pairs - 1u;
-                const uint32_t both = hist[k >> 1];
-                hist[k >> 1] = 0u;
-                lo = (int)(both & 0xffffu);
-                hi = (int)(both >> 16);
-                if (lo != 0) at = write_entries<Layout>(ent, at, k, lo);
-                if (hi != 0) at = write_entries<Layout>(ent, at, k + 1, hi);
-            }
-            add_ll(lo);
-            add_ll(hi);
-        }
         const bool real = 2 * i + half < D;              // the last pair may lack its second document
+        const int n_longer = max(n_a, n_b);
+        if (__ballot(mine != distinct) == 0 && n_longer <= kPairStage) {
+            // The usual case, every topic one entry: the lanes that own the bins only line the
+            // entries up in LDS; the lanes then take them one each, so that the row leaves in
+            // whole consecutive stores and the likelihood's term is added with all lanes busy.
+            while (__ballot(pairs != 0u) != 0) {
+                if (pairs != 0u) {
+                    const int k = hl * 32 + __ffs((int)pairs) - 1;    // even topic of the pair
+                    pairs &= pairs - 1u;
+                    const uint32_t both = hist[k >> 1];
+                    hist[k >> 1] = 0u;
+                    const int lo = (int)(both & 0xffffu), hi = (int)(both >> 16);
+                    if (lo != 0) stage[at++] = Layout::make(lo, k);
+                    if (hi != 0) stage[at++] = Layout::make(hi, k + 1);
+                }
+            }
+            __syncthreads();
+            for (int first = 0; first < n_longer; first += 32) {
+                const int e = first + hl;
+                int c = 0;
+                if (e < n_entries) {
+                    const Entry v = stage[e];
+                    ent[e] = v;
+                    c = Layout::entry_count(v);
+                }
+                add_ll(c);
+            }
+        } else {
+            while (__ballot(pairs != 0u) != 0) {
+                int lo = 0, hi = 0;
+                if (pairs != 0u) {
+                    const int k = hl * 32 + __ffs((int)pairs) - 1;    // even topic of the pair
+                    pairs &= pairs - 1u;
+                    const uint32_t both = hist[k >> 1];
+                    hist[k >> 1] = 0u;
+                    lo = (int)(both & 0xffffu);
+                    hi = (int)(both >> 16);
+                    if (lo != 0) at = write_entries<Layout>(ent, at, k, lo);
+                    if (hi != 0) at = write_entries<Layout>(ent, at, k + 1, hi);
+                }
+                add_ll(lo);
+                add_ll(hi);
+            }
+        }
         close_row<Layout>(head, n_entries, K, hl, real);
         if (real && hl == 0) {
             row_rec[cur.doc].y = (uint32_t)nnz;          // distinct topics, for the getters
@@ -566,6 +601,44 @@ __global__ __launch_bounds__(kWave) void derive_tok_slot_kernel(const DocRec* do
     }
 }
 
+// The map entries of every document put in rising order, in runs of kMapSortRun entries (a
+// whole document if it has no more).  The rebuild counts a document's topics, so the order in
+// which it meets them is free; in rising order the tokens that share their document AND their
+// word are neighbours in the map as they are in z, neighbouring lanes then read the same line,
+// and the gather asks the caches for it once.  After this the map no longer tells a token's
+// place inside its document: only the rebuild and derive_tok_slot_kernel read it.
+// One wave per document, persistent; a bitonic network over a run held in LDS.
+constexpr int kMapSortRun = 256;
+__global__ __launch_bounds__(kWave) void sort_doc_map_kernel(const DocRec* docs, int64_t D, int32_t* doc_map) {
+    __shared__ int32_t run[kMapSortRun];
+    const int lane = (int)threadIdx.x;
+    for (int64_t i = blockIdx.x; i < D; i += gridDim.x) {
+        const DocRec r = docs[i];
+        for (int base = 0; base < r.n; base += kMapSortRun) {
+            const int n = min(kMapSortRun, r.n - base);
+            if (n < 2) continue;
+            // the smallest power of two that holds the run; places past its end sort last
+            int width = 2;
+            while (width < n) width <<= 1;
+            for (int e = lane; e < width; e += kWave)
+                run[e] = e < n ? doc_map[r.begin + base + e] : 0x7fffffff;
+            __syncthreads();
+            for (int k = 2; k <= width; k <<= 1)
+                for (int j = k >> 1; j > 0; j >>= 1) {
+                    for (int pair = lane; pair < width / 2; pair += kWave) {
+                        const int lo = ((pair & ~(j - 1)) << 1) | (pair & (j - 1)), hi = lo | j;
+                        const int32_t a = run[lo], b = run[hi];
+                        const bool rising = (lo & k) == 0;
+                        if ((a > b) == rising) { run[lo] = b; run[hi] = a; }
+                    }
+                    __syncthreads();
+                }
+            for (int e = lane; e < n; e += kWave) doc_map[r.begin + base + e] = run[e];
+            __syncthreads();
+        }
+    }
+}
+
 // A chunk without a map (its assignments arrive in document order): every token's topic is
 // paired with the slot of its document's theta row, one wave per document, persistent, where
 // both are contiguous ...
@@ -590,15 +663,7 @@ __global__ void pairs_to_word_major_kernel(const uint2* pairs, const int32_t* to
     z_word[pos] = (uint16_t)p.y;
 }
 
-// Boundary order changes.  doc_map[t] = word-major position of document-major token t;
-// tok_id[pos] = document-major index of word-major position pos.
-__global__ void to_doc_major_kernel(const uint16_t* z_word, const int32_t* doc_map,
-                                    uint16_t* z_doc, int64_t T) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < T) z_doc[t] = z_word[doc_map[t]];
-}
-
-// The same order change as a scatter, for when there is no map.
+// Boundary order changes.  tok_id[pos] = document-major index of word-major position pos.
 __global__ void to_doc_major_scatter_kernel(const uint16_t* z_word, const int32_t* tok_id,
                                             uint16_t* z_doc, int64_t T, int64_t first) {
     const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -589,6 +589,9 @@ void derive_chunk_arrays(mlda_ctx* c) {
         const int grid = (int)std::min<int64_t>(c->D, (int64_t)c->n_cus * 32);
         hipLaunchKernelGGL(mlda::derive_tok_slot_kernel, dim3((unsigned)grid), dim3(mlda::kWave), 0, c->stream,
                            c->doc_order, c->D, c->doc_map, c->tok_slot);
+        // from here on the map lists a document's tokens by rising place in z
+        hipLaunchKernelGGL(mlda::sort_doc_map_kernel, dim3((unsigned)grid), dim3(mlda::kWave), 0, c->stream,
+                           c->doc_order, c->D, c->doc_map);
     }
     const uint32_t pad = c->tiny ? (uint32_t)mlda::TinyRows::make(0, c->K) * 0x10001u
                                  : (uint32_t)mlda::PackedRows::make(0, c->K);
@@ -728,7 +731,7 @@ int rebuild_theta(mlda_ctx* c, const uint16_t* z) {
         const void* kernel =
             pairs ? (c->tiny ? (const void*)theta_rows_pair_kernel<TinyRows> : (const void*)theta_rows_pair_kernel<PackedRows>)
                   : theta_kernel_for(c->tiny, c->wide_counters);
-        const size_t lds = pairs ? 2 * theta_hist_bytes(c->K, false) + (size_t)kThetaLgTable * 8 : theta_lds;
+        const size_t lds = pairs ? theta_pair_lds_bytes(c->K) : theta_lds;
         const DocRec* docs = c->doc_order;
         uint2* row_rec = c->row_rec;
         unsigned char* slots = c->slots;
@@ -1435,8 +1438,8 @@ int mlda_get_assignments(mlda_ctx* c, uint16_t* z) {
         return MLDA_OK;
     }
     uint16_t* tmp = c->z[c->cur ^ 1];      // free between steps
-    hipLaunchKernelGGL(mlda::to_doc_major_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
-                       c->z[c->cur], c->doc_map, tmp, c->T);
+    hipLaunchKernelGGL(mlda::to_doc_major_scatter_kernel, dim3(blocks_for(c->T, 256)), dim3(256), 0, c->stream,
+                       c->z[c->cur], c->tok_id, tmp, c->T, c->at->tok_begin);
     HIP_TRY(hipMemcpyAsync(z, tmp, (size_t)c->T * 2, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return MLDA_OK;
