@@ -74,6 +74,10 @@ struct SampleArgs {
     double alpha, beta, beta_V;
     uint64_t seed;
     uint32_t iter;
+    // Workgroup b < n_single takes tile b.  The tiles from n_single on each hold a whole word of
+    // few tokens; a workgroup takes a run of run_tiles of them, one after the other, and turns
+    // p* of one word into p* of the next instead of staging it afresh (run_tiles <= 1: no runs).
+    int32_t n_tiles, n_single, run_tiles;
 };
 
 constexpr int kRowHeader = 16;  // bytes before a theta row's entries
@@ -103,6 +107,13 @@ __host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
     return (size_t)Kpad * 4 + (size_t)((Kpad / dense_group(waves) + 1) & ~1) * 8 +
            (size_t)waves * kWave * sizeof(TokenRec);
 }
+// What runs of small tiles keep in LDS besides: the groups' own sums (the prefix sums are made
+// from them again after every change) and one bit per group for "changed".
+__host__ __device__ constexpr size_t sample_run_lds_bytes(int Kpad, int waves) {
+    const size_t ng = (size_t)(Kpad / dense_group(waves));
+    return ((ng + 1) & ~(size_t)1) * 8 + ((ng + 31) / 32 * 4 + 15 & ~(size_t)15);
+}
+constexpr int kRunTileTokens = 1024;    // a tile of a run holds a whole word of at most this many tokens
 
 // Dense bucket (p2 = alpha p*', Eq. 6): smallest k with alpha * prefix'(k) > y, where
 // prefix' is the prefix sum of p* with the entry of the token's own topic o replaced by
@@ -567,7 +578,22 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     unsigned char* wave_base = lds + (size_t)Kpad * 4 + (size_t)((ng + 1) & ~1) * 8;
     TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base) + wave * kWave;
 
-    Tile tl = a.tiles[blockIdx.x];         // the same for every lane: keep it in SGPRs
+    // The workgroup's tiles: one, or (large K only) a run of small ones.  What says where the
+    // run starts and ends is worked out again where it is needed rather than kept through the
+    // token phase, whose registers are all taken.
+    constexpr bool kRuns = kWaves == 12;
+    auto in_run = [&]() { return kRuns && (int)blockIdx.x >= a.n_single; };
+    auto first_tile = [&]() {
+        return in_run() ? a.n_single + ((int)blockIdx.x - a.n_single) * a.run_tiles : (int)blockIdx.x;
+    };
+    auto last_tile = [&]() { return in_run() ? min(first_tile() + a.run_tiles, a.n_tiles) : first_tile() + 1; };
+    double* group_sum = reinterpret_cast<double*>(wave_base + (size_t)kWaves * kWave * sizeof(TokenRec));
+    uint32_t* changed = reinterpret_cast<uint32_t*>(group_sum + ((ng + 1) & ~1));
+    if (in_run()) {
+        for (int w = tid; w < (ng + 31) / 32; w += kWaves * kWave) changed[w] = 0u;
+    }
+    for (int ti = first_tile();;) {
+    Tile tl = a.tiles[ti];                 // the same for every lane: keep it in SGPRs
     tl.word = __builtin_amdgcn_readfirstlane(tl.word);
     tl.begin = __builtin_amdgcn_readfirstlane(tl.begin);
     tl.count = __builtin_amdgcn_readfirstlane(tl.count);
@@ -579,6 +605,50 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     const size_t phi_cell0 = (size_t)(wide ? wide_row : tl.word) * (size_t)K;
     const uint32_t phi_shift = wide ? 2u : 1u, phi_mask = wide ? 0xffffffffu : 0xffffu;
 
+    if (kRuns && ti > first_tile()) {
+        const Tile prev = a.tiles[ti - 1];
+        const int prev_begin = __builtin_amdgcn_readfirstlane(prev.begin);
+        const int prev_count = __builtin_amdgcn_readfirstlane(prev.count);
+        // ---- p* of the run's previous word becomes p* of this one.  Both words have all their
+        // tokens in their tile, so a cell of phi is non-zero exactly for the topics of the
+        // tile's tokens: only those cells differ from beta / (n_k + beta V).  Every changed cell
+        // gets the value a fresh staging would give it, and the sums of the groups that hold
+        // one are added up again in the same order, so the result is the fresh staging's, bit
+        // for bit.
+        for (int idx = tid; idx < prev_count; idx += kWaves * kWave) {
+            const int k = (int)a.z_cur[prev_begin + idx];
+            pstar[k] = (float)((0.0 + a.beta) / ((double)a.n_k[k] + a.beta_V));
+            atomicOr(&changed[(k / kGroup) >> 5], 1u << ((k / kGroup) & 31));
+        }
+        __syncthreads();
+        const uint16_t* phi_v = reinterpret_cast<const uint16_t*>(phi_cells) + phi_cell0;   // (never a wide row)
+        for (int idx = tid; idx < tl.count; idx += kWaves * kWave) {
+            const int k = (int)a.z_cur[tl.begin + idx];
+            pstar[k] = (float)(((double)phi_v[k] + a.beta) / ((double)a.n_k[k] + a.beta_V));
+            atomicOr(&changed[(k / kGroup) >> 5], 1u << ((k / kGroup) & 31));
+        }
+        __syncthreads();
+        for (int g = tid; g < ng; g += kWaves * kWave)
+            if ((changed[g >> 5] >> (g & 31)) & 1u) {
+                double s = 0.0;
+#pragma unroll
+                for (int j = 0; j < kGroup; ++j) s += (double)pstar[g * kGroup + j];
+                group_sum[g] = s;
+            }
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = lane; w < (ng + 31) / 32; w += kWave) changed[w] = 0u;
+            double carry = 0.0;
+            for (int base = 0; base < ng; base += kWave) {
+                const int g = base + lane;
+                double x = (g < ng) ? group_sum[g] : 0.0;
+                x = wave_inclusive_sum(x) + carry;
+                if (g < ng) cp[g] = x;
+                carry = read_lane(x, kWave - 1);
+            }
+        }
+        __syncthreads();
+    } else {
     // ---- stage p*(k) = (phi_kv + beta)/(n_k + beta V) as fp32 (Eq. 8)
     if (wide) {
         const int32_t* phi_v = reinterpret_cast<const int32_t*>(phi_cells) + phi_cell0;
@@ -601,6 +671,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) s += (double)pstar[g * kGroup + j];
         cp[g] = s;
+        if (in_run()) group_sum[g] = s;
     }
     __syncthreads();
     if (wave == 0) {                       // inclusive prefix over the group sums
@@ -614,6 +685,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         }
     }
     __syncthreads();
+    }
 
     // a pass shape's lane geometry: token of the lane relative to the pass's first, the lane's
     // place inside its group, its first unit of entries
@@ -769,6 +841,10 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+    }
+    ti += 1;
+    if (!kRuns || ti >= last_tile()) break;
+    __syncthreads();                // every wave is done with this word's p*
     }
 }
 

@@ -73,6 +73,7 @@ const void* theta_kernel_for(bool tiny, bool wide_counters) {
                          : (const void*)mlda::theta_rows_kernel<mlda::PackedRows, false>;
 }
 constexpr int kMaxTimedIters = 1024;
+constexpr int kRunTiles = 16;           // small tiles a workgroup of the large-K sampler takes one after the other
 // events of a streamed chunk visit: its uploads have arrived | topics and slots in word-major
 // order | theta rebuilt | sampled | phi added to | new topics in document order | theta of the
 // new topics (log-likelihood)
@@ -210,6 +211,7 @@ struct HostChunk {
     bool short_docs = true;             // no document has more tokens than a 4-byte entry counts
     size_t slots_bytes = 0;
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
+    int32_t n_single = 0;               // the tiles from this one on hold whole small words: taken in runs
     int32_t n_wide_tiles = 0;           // sampling tiles of words whose row of phi is int32
     ChunkLayout L;
     unsigned char* arena = nullptr;     // L.static_bytes bytes
@@ -233,7 +235,7 @@ struct HostChunk {
 // result, because the uniforms are keyed by the caller's token index.  `accumulate`: the
 // chunk's counts will be added to phi (several chunks) instead of stored.
 int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64_t d_begin,
-                  int64_t d_end, int32_t V, int32_t K, bool accumulate, bool pinned, HostChunk& h) {
+                  int64_t d_end, int32_t V, int32_t K, bool accumulate, bool pinned, bool runs, HostChunk& h) {
     const int64_t D = d_end - d_begin;
     const int64_t tok_begin = doc_ptr_all[d_begin];
     const int64_t T = doc_ptr_all[d_end] - tok_begin;
@@ -409,6 +411,16 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
         });
         std::stable_sort(segs, segs + n_segs,
                          [](const mlda::Tile& a, const mlda::Tile& b) { return a.count > b.count; });
+        // tiles that hold a whole word of few tokens go last, to be taken in runs by one
+        // workgroup each (their order among themselves stays)
+        h.n_single = h.n_tiles;
+        if (runs) {
+            mlda::Tile* first_small = std::stable_partition(tiles, tiles + n_tiles, [&](const mlda::Tile& t) {
+                const bool whole_word = word_ptr[t.word + 1] - word_ptr[t.word] == t.count;
+                return !(whole_word && t.count <= mlda::kRunTileTokens);
+            });
+            h.n_single = (int32_t)(first_small - tiles);
+        }
     } catch (const std::bad_alloc&) {
         return fail(MLDA_ENOMEM, "out of host memory");
     }
@@ -491,6 +503,8 @@ struct mlda_ctx {
     mlda::Tile* tiles = nullptr;         // sampling tiles
     mlda::Tile* segs = nullptr;          // phi rebuild segments
     int32_t n_tiles = 0, n_segs = 0, n_split = 0, n_wide_tiles = 0;
+    int32_t n_single = 0;                // tiles taken one per workgroup; the rest in runs of run_tiles
+    int32_t run_tiles = 1;
 
     int static_device = -1;              // >= 0: the workspace is that device's static array
 };
@@ -552,6 +566,7 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->slots_bytes = h.slots_bytes;
     c->n_tiles = h.n_tiles; c->n_segs = h.n_segs; c->n_split = h.n_split;
     c->n_wide_tiles = h.n_wide_tiles;
+    c->n_single = h.n_single;
     c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
     c->tok_id = (int32_t*)(base + h.L.tok_id);
     c->doc_map = (int32_t*)(base + h.L.doc_map);
@@ -765,9 +780,13 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     a.beta_V = c->beta * (double)c->V;
     a.seed = c->seed;
     a.iter = (uint32_t)(c->iter + 1);
+    a.n_tiles = c->n_tiles;
+    a.n_single = c->run_tiles > 1 ? c->n_single : c->n_tiles;
+    a.run_tiles = c->run_tiles;
     const int waves = sample_waves_for(c->K);
+    const int32_t grid = a.n_single + (a.n_tiles - a.n_single + a.run_tiles - 1) / a.run_tiles;
     void* kernel_args[] = {&a};
-    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs), dim3((unsigned)c->n_tiles),
+    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs), dim3((unsigned)grid),
                             dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
     return launch_check("sample_kernel");
 }
@@ -893,8 +912,10 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     RC_TRY(launch_check("model set-up kernels"));
     if (c->sample_lds > 48 * 1024)
         for (bool short_docs : {false, true})
+            // (the attribute belongs to the kernel, not to this context: contexts of different
+            // needs may live side by side, so it is raised to what the device allows)
             HIP_TRY(hipFuncSetAttribute(sample_kernel_for(c->K, short_docs),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->sample_lds));
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
     if ((size_t)c->K * 4 > 48 * 1024) {
         HIP_TRY(hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
@@ -961,6 +982,17 @@ int device_limits(mlda_ctx* c) {
         return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " needs " + std::to_string(c->sample_lds) +
                                       " bytes of LDS per workgroup, the device allows " +
                                       std::to_string(c->lds_limit));
+    // Large K, corpus resident (so that phi holds exactly the attached tokens): the many words
+    // of few tokens are sampled in runs, one workgroup turning p* of one word into p* of the
+    // next.  That takes a little more LDS; not if it would cost the CU its second workgroup.
+    c->run_tiles = 1;
+    const size_t with_runs = c->sample_lds + mlda::sample_run_lds_bytes(c->Kpad, sample_waves_for(c->K));
+    const size_t cu_lds = 160 * 1024;
+    if (sample_waves_for(c->K) == 12 && !c->streamed && with_runs <= (size_t)c->lds_limit &&
+        (2 * with_runs <= cu_lds || 2 * c->sample_lds > cu_lds)) {
+        c->sample_lds = with_runs;
+        c->run_tiles = kRunTiles;
+    }
     return MLDA_OK;
 }
 
@@ -1155,7 +1187,7 @@ static int create_resident(mlda_ctx** out, const int64_t* doc_ptr, const int32_t
     if (rc == MLDA_OK) {
         try { c->chunks = std::vector<HostChunk>(1); } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
     }
-    if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->chunks[0]);
+    if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->run_tiles > 1, c->chunks[0]);
     if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[0]);
     const ModelLayout ML = model_layout(V, K, T, false);
     if (rc == MLDA_OK && ML.total + c->chunks[0].L.total > workspace_bytes)
@@ -1223,7 +1255,7 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     size_t chunk_bytes = 0;
     for (int32_t m = 0; rc == MLDA_OK && m < n_chunks; ++m) {
         rc = prepare_chunk(doc_ptr, word_ids, chunk_first(doc_ptr, D, n_chunks, m),
-                           chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, c->chunks[(size_t)m]);
+                           chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, false, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) chunk_bytes = std::max(chunk_bytes, c->chunks[(size_t)m].L.total);
     }
