@@ -581,10 +581,18 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     // The workgroup's tiles: one, or (large K only) a run of small ones.  What says where the
     // run starts and ends is worked out again where it is needed rather than kept through the
     // token phase, whose registers are all taken.
+    // Runs are dealt evenly among the other workgroups in launch order (the runs wait for memory
+    // most of the time, the large tiles keep the arithmetic units busy: side by side on a CU they
+    // fill each other's gaps): of the workgroups before b, floor(b * n_runs / grid) take a run.
     constexpr bool kRuns = kWaves == 12;
-    auto in_run = [&]() { return kRuns && (int)blockIdx.x >= a.n_single; };
+    auto runs_before = [&](int b) {
+        const int n_runs = (int)gridDim.x - a.n_single;
+        return (int)((int64_t)b * n_runs / (int64_t)gridDim.x);
+    };
+    auto in_run = [&]() { return kRuns && runs_before((int)blockIdx.x + 1) > runs_before((int)blockIdx.x); };
     auto first_tile = [&]() {
-        return in_run() ? a.n_single + ((int)blockIdx.x - a.n_single) * a.run_tiles : (int)blockIdx.x;
+        const int before = kRuns ? runs_before((int)blockIdx.x) : 0;
+        return in_run() ? a.n_single + before * a.run_tiles : (int)blockIdx.x - before;
     };
     auto last_tile = [&]() { return in_run() ? min(first_tile() + a.run_tiles, a.n_tiles) : first_tile() + 1; };
     double* group_sum = reinterpret_cast<double*>(wave_base + (size_t)kWaves * kWave * sizeof(TokenRec));
