@@ -197,8 +197,11 @@ int mlda_get_timing(mlda_ctx* ctx, double* ms, int32_t capacity_iters, int32_t* 
  * topic and four of count, else 4 bytes, sixteen bits of topic and fourteen of count; a count
  * beyond its field takes several entries), plus the word's row of phi per tile: 2 K bytes
  * (Section 6.1.3: short integers), 4 K for a word with 2^16 tokens or more, whose counts the
- * library keeps as int32.  bytes: host, capacity_iters doubles, out; rows as in
- * mlda_get_timing.
+ * library keeps as int32.  With K > 2048 the words of at most 1024 tokens are sampled in runs
+ * of 16 by one workgroup, which derives every following word's p* from the one before: such
+ * a word then counts, instead of a row of phi, 6 bytes per token (the topics of the word
+ * before it, and topic and cell of phi of its own tokens).  bytes: host, capacity_iters
+ * doubles, out; rows as in mlda_get_timing.
  */
 int mlda_get_sampler_bytes(mlda_ctx* ctx, double* bytes, int32_t capacity_iters, int32_t* n_iters);
 

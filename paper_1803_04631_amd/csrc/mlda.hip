@@ -212,6 +212,7 @@ struct HostChunk {
     size_t slots_bytes = 0;
     int32_t n_tiles = 0, n_segs = 0, n_split = 0;
     int32_t n_single = 0;               // the tiles from this one on hold whole small words: taken in runs
+    int64_t run_tokens = 0;             // their tokens
     int32_t n_wide_tiles = 0;           // sampling tiles of words whose row of phi is int32
     ChunkLayout L;
     unsigned char* arena = nullptr;     // L.static_bytes bytes
@@ -420,6 +421,8 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
                 return !(whole_word && t.count <= mlda::kRunTileTokens);
             });
             h.n_single = (int32_t)(first_small - tiles);
+            h.run_tokens = 0;
+            for (const mlda::Tile* t = first_small; t < tiles + n_tiles; ++t) h.run_tokens += t->count;
         }
     } catch (const std::bad_alloc&) {
         return fail(MLDA_ENOMEM, "out of host memory");
@@ -505,6 +508,7 @@ struct mlda_ctx {
     int32_t n_tiles = 0, n_segs = 0, n_split = 0, n_wide_tiles = 0;
     int32_t n_single = 0;                // tiles taken one per workgroup; the rest in runs of run_tiles
     int32_t run_tiles = 1;
+    int64_t run_tokens = 0;              // tokens of the tiles taken in runs
 
     int static_device = -1;              // >= 0: the workspace is that device's static array
 };
@@ -567,6 +571,7 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
     c->n_tiles = h.n_tiles; c->n_segs = h.n_segs; c->n_split = h.n_split;
     c->n_wide_tiles = h.n_wide_tiles;
     c->n_single = h.n_single;
+    c->run_tokens = h.run_tokens;
     c->tok_slot = (uint32_t*)(base + h.L.tok_slot);
     c->tok_id = (int32_t*)(base + h.L.tok_id);
     c->doc_map = (int32_t*)(base + h.L.doc_map);
@@ -1630,9 +1635,16 @@ int mlda_get_sampler_bytes(mlda_ctx* c, double* bytes, int32_t capacity_iters, i
         const int64_t r = c->rebuilds - c->last_step_iters + j - 1;
         const double row_entries = c->D > 0 ? (double)ring[(size_t)(r % kEntryRing)] : 0.0;
         // per token: row slot 4, token id 4, old topic 2, new topic 2, row length 4
-        // per tile: the word's row of phi, 2 K bytes, or 4 K for a word with 2^16 tokens or more
+        // per tile: the word's row of phi, 2 K bytes, or 4 K for a word with 2^16 tokens or more;
+        // a tile that follows another in a run reads, instead of a row of phi, the topics of
+        // the previous tile's tokens and, for its own tokens, topic and cell of phi: 6 bytes
+        // per token, counted as if both tiles had this tile's tokens
+        const int32_t n_run_tiles = c->run_tiles > 1 ? c->n_tiles - c->n_single : 0;
+        const int32_t n_runs = n_run_tiles > 0 ? (n_run_tiles + c->run_tiles - 1) / c->run_tiles : 0;
+        const double staged_rows = (double)(c->n_tiles - n_run_tiles + n_runs);
         bytes[i] = 16.0 * (double)c->T + entry_bytes * row_entries +
-                   (double)c->K * (2.0 * (double)c->n_tiles + 2.0 * (double)c->n_wide_tiles);
+                   (double)c->K * (2.0 * staged_rows + 2.0 * (double)c->n_wide_tiles) +
+                   6.0 * (double)c->run_tokens;
     }
     *n_iters = n;
     return MLDA_OK;

@@ -113,6 +113,9 @@ EDGE_CASES = [
     ("one_word_vocab",      40,  1,    8,   20),
     ("large_k_small_docs",  300, 2000, 10000, 120),   # C5-like K: 45 KB of LDS per tile
     ("short_docs",          3000, 200, 16,  1.2),     # many single-token documents (S = 0)
+    # large K, words of every size: several tiles, one tile of more than 1024 tokens, and
+    # small ones, which one workgroup takes in runs of 16 (p* of a word derived from the word before)
+    ("large_k_mixed_words", 400, 70,   3000, 300),
     ("k_twenty_thousand",   40,  300,  20000, 400),   # every kernel beyond 64 KB of LDS
     ("k_near_lds_limit",    40,  300,  30800, 400),   # 160 KB of LDS: one workgroup per CU
     # long documents over few topics: counts far beyond one entry's field are spread over
@@ -410,6 +413,30 @@ def test_step_with_loglik_flag_and_timing(mlda):
                 + cfg.K * (2.0 * n_tiles + 2.0 * n_wide_tiles))
         assert b == want
     assert len(got) == 2
+    model.close()
+
+
+def test_sampler_bytes_with_runs_of_small_words(mlda):
+    """K > 2048: the words of at most 1024 tokens are sampled in runs of 16 and count 6 bytes per
+    token instead of a row of phi each, but for the first word of every run."""
+    D, V, K = 300, 500, 4000
+    c = corpus_synth.tiny(D=D, V=V, K=K, mean_len=200, seed=21, name="runs")
+    alpha, beta = 50.0 / K, 0.01
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, SEED)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, SEED)
+    z = check_step(model, c, z, V, K, alpha, beta, SEED, 1)
+    row_ptr, _, _ = oracle.doc_topic_csr(c.doc_ptr, oracle.init_topics(c.T, K, SEED), K)
+    lens = np.diff(c.doc_ptr)
+    per_word = np.bincount(c.word_ids, minlength=V)
+    per_word = per_word[per_word > 0]
+    n_tiles = int(np.ceil(per_word / 4096).sum())
+    in_runs = per_word[per_word <= 1024]
+    assert 16 < len(in_runs) < len(per_word)          # runs, and words outside them
+    staged_rows = n_tiles - len(in_runs) + -(-len(in_runs) // 16)
+    want = (16.0 * c.T + 4.0 * float((lens * np.diff(row_ptr)).sum())
+            + K * 2.0 * staged_rows + 6.0 * float(in_runs.sum()))
+    assert model.sampler_bytes()[-1] == want
     model.close()
 
 
