@@ -56,12 +56,13 @@ extern "C" {
                               2^31 or more tokens, topic >= K) */
 #define MLDA_ENOMEM   -2   /* device workspace smaller than mlda_workspace_bytes, or host malloc failed */
 #define MLDA_EHIP     -3   /* a HIP call failed; the message names it */
-#define MLDA_ENOTSUP  -4   /* K too large for this device's LDS: the sampler keeps the word's column of p*
-                              (Eq. 8: 4 K bytes, plus K/2 bytes of prefix sums and its waves' records) in
-                              the 160 KB a workgroup may use, which holds K up to about 30,800.  Topic
-                              indices are 16-bit (Section 6.1.3), so K up to 65,535 is well-formed, but
-                              beyond that limit mlda_create refuses; the paper's own range is 1,000 to
-                              10,000 (Section 2.1) */
+#define MLDA_ENOTSUP  -4   /* the one combination that exceeds the 160 KB of LDS a workgroup may use: K beyond
+                              about 39,000 together with a document of 2^16 tokens or more (the theta
+                              rebuild then needs a 32-bit counter per topic in LDS).  Every other K up to
+                              65,535, the range of the 16-bit topic index (Section 6.1.3), is served: up to
+                              about 30,900 the sampler keeps the word's column of p* (Eq. 8) in LDS, beyond
+                              that in device memory, several times slower; the paper's own range is 1,000
+                              to 10,000 (Section 2.1) */
 
 #define MLDA_STEP_LOGLIK 1u /* mlda_step flag: also evaluate the log-likelihood after each iteration */
 
@@ -82,10 +83,11 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
  *   hip_stream     a hipStream_t (0 = the default stream).
  * The corpus is copied; the host arrays may be released after the call.  No
  * topics are assigned yet: call mlda_init_random or mlda_set_assignments next.
- * K: 1 .. 65,535 is accepted as an argument (MLDA_EINVAL outside); a K whose column of p* does
- * not fit the device's LDS (about 30,800 on MI355X) returns MLDA_ENOTSUP, and the message
- * names the bytes needed and allowed.  mlda_workspace_bytes does not look at the device and
- * answers for any K in the argument range.
+ * K: 1 .. 65,535 (MLDA_EINVAL outside).  A K whose column of p* does not fit the 160 KB of LDS
+ * of a workgroup (beyond about 30,900) is sampled with p* in device memory: same results, several
+ * times slower per token; the workspace then holds 512 such columns more.  MLDA_ENOTSUP only for
+ * K beyond about 39,000 with a document of 2^16 tokens or more; the message names the bytes
+ * needed and allowed.
  */
 int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                 int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,

@@ -29,41 +29,52 @@ __global__ void zero_rows_kernel(const int32_t* words, PhiView phi, int32_t K) {
 // the word's row outright if the segment is the whole word, else adds its non-zero bins
 // to the row.  A 16-bit cell is added to through the aligned dword that holds it: the word has
 // fewer than 2^16 tokens, so no sum carries into the neighbouring cell.
+// kRange: K counters do not fit a workgroup's LDS; the launch then covers the topics
+// k_lo .. k_lo + kn - 1 only (one launch per such range), else all K.
+template <bool kRange>
 __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const uint16_t* z,
-                                                       PhiView phi, int32_t K) {
+                                                       PhiView phi, int32_t K, int32_t k_lo, int32_t kn) {
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* hist = reinterpret_cast<int32_t*>(lds);
     const Tile tl = segs[blockIdx.x];
     const int tid = (int)threadIdx.x;
-    for (int k = tid; k < K; k += 256) hist[k] = 0;
+    const int lo = kRange ? k_lo : 0, n = kRange ? kn : K;
+    for (int k = tid; k < n; k += 256) hist[k] = 0;
     __syncthreads();
     // four independent loads in flight per thread: the loop is bound by their latency
     const uint16_t* zt = z + tl.begin;
     int i = tid;
-    for (; i + 768 < tl.count; i += 1024) {
-        const int k0 = zt[i], k1 = zt[i + 256], k2 = zt[i + 512], k3 = zt[i + 768];
-        atomicAdd(&hist[k0], 1); atomicAdd(&hist[k1], 1); atomicAdd(&hist[k2], 1); atomicAdd(&hist[k3], 1);
+    if (kRange) {
+        for (; i < tl.count; i += 256) {
+            const int k = (int)zt[i] - lo;
+            if ((unsigned)k < (unsigned)n) atomicAdd(&hist[k], 1);
+        }
+    } else {
+        for (; i + 768 < tl.count; i += 1024) {
+            const int k0 = zt[i], k1 = zt[i + 256], k2 = zt[i + 512], k3 = zt[i + 768];
+            atomicAdd(&hist[k0], 1); atomicAdd(&hist[k1], 1); atomicAdd(&hist[k2], 1); atomicAdd(&hist[k3], 1);
+        }
+        for (; i < tl.count; i += 256) atomicAdd(&hist[zt[i]], 1);
     }
-    for (; i < tl.count; i += 256) atomicAdd(&hist[zt[i]], 1);
     __syncthreads();
     const int wide_row = phi.wide_row[tl.word];
     if (wide_row >= 0) {
-        int32_t* row = phi.wide + (size_t)wide_row * (size_t)K;
+        int32_t* row = phi.wide + (size_t)wide_row * (size_t)K + lo;
         if (tl.whole) {
-            for (int k = tid; k < K; k += 256) row[k] = hist[k];
+            for (int k = tid; k < n; k += 256) row[k] = hist[k];
         } else {
-            for (int k = tid; k < K; k += 256) {
+            for (int k = tid; k < n; k += 256) {
                 const int c = hist[k];
                 if (c != 0) atomicAdd(&row[k], c);
             }
         }
     } else {
-        const size_t cell0 = (size_t)tl.word * (size_t)K;
+        const size_t cell0 = (size_t)tl.word * (size_t)K + (size_t)lo;
         if (tl.whole) {
-            for (int k = tid; k < K; k += 256) phi.narrow[cell0 + k] = (uint16_t)hist[k];
+            for (int k = tid; k < n; k += 256) phi.narrow[cell0 + k] = (uint16_t)hist[k];
         } else {
             uint32_t* dwords = reinterpret_cast<uint32_t*>(phi.narrow);
-            for (int k = tid; k < K; k += 256) {
+            for (int k = tid; k < n; k += 256) {
                 const uint32_t c = (uint32_t)hist[k];
                 const size_t cell = cell0 + k;
                 if (c != 0) atomicAdd(&dwords[cell >> 1], c << ((cell & 1) * 16));
@@ -73,21 +84,26 @@ __global__ __launch_bounds__(256) void phi_tile_kernel(const Tile* segs, const u
 }
 
 // n_k[k] = number of tokens with topic k.  Persistent workgroups, each over a contiguous
-// share of the tokens; n_k must be zero on entry.
-__global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, int64_t T,
-                                                           int32_t* n_k, int32_t K) {
+// share of the tokens; n_k must be zero on entry.  kRange as above.
+template <bool kRange>
+__global__ __launch_bounds__(256) void topic_totals_kernel(const uint16_t* z, int64_t T, int32_t* n_k,
+                                                           int32_t K, int32_t k_lo, int32_t kn) {
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* hist = reinterpret_cast<int32_t*>(lds);
     const int tid = (int)threadIdx.x;
-    for (int k = tid; k < K; k += 256) hist[k] = 0;
+    const int lo = kRange ? k_lo : 0, n = kRange ? kn : K;
+    for (int k = tid; k < n; k += 256) hist[k] = 0;
     __syncthreads();
     const int64_t per = (T + gridDim.x - 1) / gridDim.x;
-    const int64_t lo = per * blockIdx.x, hi = (lo + per < T) ? lo + per : T;
-    for (int64_t t = lo + tid; t < hi; t += 256) atomicAdd(&hist[z[t]], 1);
+    const int64_t t_lo = per * blockIdx.x, t_hi = (t_lo + per < T) ? t_lo + per : T;
+    for (int64_t t = t_lo + tid; t < t_hi; t += 256) {
+        const int k = (int)z[t] - lo;
+        if (!kRange || (unsigned)k < (unsigned)n) atomicAdd(&hist[k], 1);
+    }
     __syncthreads();
-    for (int k = tid; k < K; k += 256) {
+    for (int k = tid; k < n; k += 256) {
         const int c = hist[k];
-        if (c != 0) atomicAdd(&n_k[k], c);
+        if (c != 0) atomicAdd(&n_k[lo + k], c);
     }
 }
 

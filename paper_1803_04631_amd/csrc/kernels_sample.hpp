@@ -34,6 +34,7 @@
 //   - the row walk is a chain of dependent loads (record, then a random row in HBM), so the
 //     loads of the next pass are issued before the current pass is worked on.
 #pragma once
+#include <type_traits>
 #include "device_util.hpp"
 
 namespace mlda {
@@ -78,6 +79,9 @@ struct SampleArgs {
     // few tokens; a workgroup takes a run of run_tiles of them, one after the other, and turns
     // p* of one word into p* of the next instead of staging it afresh (run_tiles <= 1: no runs).
     int32_t n_tiles, n_single, run_tiles;
+    // K too large for p* to fit a workgroup's LDS (sample_kernel<12, .., true>): workgroup b keeps
+    // p* of its current tile in far_pstar[b * Kpad ..] and takes the tiles b, b + grid, ...
+    float* far_pstar;
 };
 
 constexpr int kRowHeader = 16;  // bytes before a theta row's entries
@@ -106,6 +110,10 @@ constexpr int kDrawTopic = -3;  // off = the new topic itself
 __host__ __device__ constexpr size_t sample_lds_bytes(int Kpad, int waves) {
     return (size_t)Kpad * 4 + (size_t)((Kpad / dense_group(waves) + 1) & ~1) * 8 +
            (size_t)waves * kWave * sizeof(TokenRec);
+}
+// The same when p* stays in device memory: the prefix sums and the waves' records only.
+__host__ __device__ constexpr size_t sample_far_lds_bytes(int Kpad, int waves) {
+    return sample_lds_bytes(Kpad, waves) - (size_t)Kpad * 4;
 }
 // What runs of small tiles keep in LDS besides: the groups' own sums (the prefix sums are made
 // from them again after every change) and one bit per group for "changed".
@@ -296,6 +304,19 @@ __device__ __forceinline__ float lds_float_at(uint32_t byte_address) {
     return *(lds_float_ptr)(uintptr_t)byte_address;
 }
 
+// Where the walk over a row finds p*(k) by the entry's key 4 k: in LDS ...
+struct LdsWeights {
+    __device__ __forceinline__ float operator()(uint32_t key) const { return lds_float_at(key); }
+};
+// ... or, when K is too large for that, in the workgroup's own strip of device memory (written by
+// the workgroup itself before a barrier, and read through the CU's own cache).
+struct FarWeights {
+    const unsigned char* base;
+    __device__ __forceinline__ float operator()(uint32_t key) const {
+        return *reinterpret_cast<const float*>(base + key);
+    }
+};
+
 // p1 = theta' p*' over the entries of one unit (Eq. 6), accumulated onto `acc` in entry order
 // (each product is exact in fp64).  The token's own topic o weighs w_o in all its entries and
 // its first entry counts one less: the token itself.  `prev_own`: the lanes whose entry before
@@ -303,9 +324,9 @@ __device__ __forceinline__ float lds_float_at(uint32_t byte_address) {
 // first" is worked out on these lane masks, by the scalar unit.)
 // This form leaves the sum at the unit's end only: every entry is added with its whole count,
 // and the lanes whose first own entry lies in the unit give w_o back once, at the end.
-template <class Layout>
-__device__ __forceinline__ void unit_sum(const uint4& raw, int o_key, float w_o, uint64_t& prev_own,
-                                         double& acc) {
+template <class Layout, class Weights>
+__device__ __forceinline__ void unit_sum(const Weights& weight_at, const uint4& raw, int o_key, float w_o,
+                                         uint64_t& prev_own, double& acc) {
     constexpr int n = Layout::kUnitEntries;
     uint64_t first_here = 0;
 #pragma unroll
@@ -315,7 +336,7 @@ __device__ __forceinline__ void unit_sum(const uint4& raw, int o_key, float w_o,
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             key[j] = Layout::key(raw, h + j);
-            w[j] = lds_float_at((uint32_t)key[j]);
+            w[j] = weight_at((uint32_t)key[j]);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -331,9 +352,9 @@ __device__ __forceinline__ void unit_sum(const uint4& raw, int o_key, float w_o,
 
 // The same with the running sum after every entry and the entries' keys kept (the first own
 // entry counts one less where it stands).
-template <class Layout>
-__device__ __forceinline__ void unit_prefix_sums(const uint4& raw, int o_key, float w_o, uint64_t& prev_own,
-                                                 double& acc, double* sums, int* keys) {
+template <class Layout, class Weights>
+__device__ __forceinline__ void unit_prefix_sums(const Weights& weight_at, const uint4& raw, int o_key, float w_o,
+                                                 uint64_t& prev_own, double& acc, double* sums, int* keys) {
     constexpr int n = Layout::kUnitEntries;
 #pragma unroll
     for (int j = 0; j < n; ++j) {
@@ -343,7 +364,7 @@ __device__ __forceinline__ void unit_prefix_sums(const uint4& raw, int o_key, fl
         const bool first = __builtin_amdgcn_inverse_ballot_w64(own_lanes & ~prev_own);
         prev_own = own_lanes;
         acc = fma((double)(Layout::count(raw, j) - (first ? 1 : 0)),
-                  (double)(own ? w_o : lds_float_at((uint32_t)key)), acc);
+                  (double)(own ? w_o : weight_at((uint32_t)key)), acc);
         sums[j] = acc;
         keys[j] = key;
     }
@@ -399,8 +420,9 @@ __device__ __forceinline__ void record_dense(TokenRec* rec, int sl, const RowDra
 // the draw records which unit holds it and the rest of the draw there.
 // Rows with one entry per topic, already loaded: every lane keeps the running sum after each of
 // its entries, and the lane that holds the draw finds its entry at once.
-template <class Layout, int kLanes, int kUnits>
-__device__ __forceinline__ void row_pass_searched(TokenRec* rec, int sl, const uint4* raw, int lane) {
+template <class Layout, int kLanes, int kUnits, class Weights>
+__device__ __forceinline__ void row_pass_searched(const Weights& weight_at, TokenRec* rec, int sl,
+                                                  const uint4* raw, int lane) {
     constexpr int UE = Layout::kUnitEntries, n = kUnits * UE;
     const RowCtx r = row_ctx(rec);
     double sums[n];
@@ -412,7 +434,7 @@ __device__ __forceinline__ void row_pass_searched(TokenRec* rec, int sl, const u
 #pragma unroll
         for (int j = 0; j < UE; ++j) {
             key[j] = Layout::key(raw[c], j);
-            w[j] = lds_float_at((uint32_t)key[j]);
+            w[j] = weight_at((uint32_t)key[j]);
         }
 #pragma unroll
         for (int j = 0; j < UE; ++j) {
@@ -445,11 +467,11 @@ __device__ __forceinline__ void row_pass_searched(TokenRec* rec, int sl, const u
     record_dense(rec, sl, d);
 }
 
-template <class Layout, int kLanes, int kUnits>
-__device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, int first_unit, const uint4* raw,
-                                              int lane) {
+template <class Layout, int kLanes, int kUnits, class Weights>
+__device__ __forceinline__ void row_pass_kept(const Weights& weight_at, TokenRec* rec, int sl, int first_unit,
+                                              const uint4* raw, int lane) {
     if constexpr (Layout::kOneEntryPerTopic) {
-        row_pass_searched<Layout, kLanes, kUnits>(rec, sl, raw, lane);
+        row_pass_searched<Layout, kLanes, kUnits>(weight_at, rec, sl, raw, lane);
         return;
     }
     const RowCtx r = row_ctx(rec);
@@ -461,7 +483,7 @@ __device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, int first_u
     double acc = 0.0;
 #pragma unroll
     for (int c = 0; c < kUnits; ++c) {
-        unit_sum<Layout>(raw[c], r.o_key, r.w_o, prev_own, acc);
+        unit_sum<Layout>(weight_at, raw[c], r.o_key, r.w_o, prev_own, acc);
         at_end[c] = acc;
     }
     const RowDraw d = row_draw<kLanes>(acc, rec, sl, lane);
@@ -495,9 +517,9 @@ __device__ __forceinline__ void row_pass_kept(TokenRec* rec, int sl, int first_u
 
 // The entry of one unit that holds the draw y (measured from the unit's start): the first
 // whose running sum exceeds y, else (rounding) the last one with weight.  One token per lane.
-template <class Layout>
-__device__ __forceinline__ int topic_in_unit(const unsigned char* slots, uint32_t unit, int o_key,
-                                             float w_o, double y) {
+template <class Layout, class Weights>
+__device__ __forceinline__ int topic_in_unit(const Weights& weight_at, const unsigned char* slots, uint32_t unit,
+                                             int o_key, float w_o, double y) {
     constexpr int n = Layout::kUnitEntries;
     const unsigned char* p = slots + (size_t)unit * 16u;
     const uint4 raw = *reinterpret_cast<const uint4*>(p);
@@ -513,7 +535,7 @@ __device__ __forceinline__ int topic_in_unit(const unsigned char* slots, uint32_
         prev_own = own_lanes;
         const double before = acc;
         acc = fma((double)(Layout::count(raw, j) - (first ? 1 : 0)),
-                  (double)(own ? w_o : lds_float_at((uint32_t)key)), acc);
+                  (double)(own ? w_o : weight_at((uint32_t)key)), acc);
         if (acc > before) last = key;
         if (found < 0 && acc > y) found = key;
     }
@@ -522,8 +544,9 @@ __device__ __forceinline__ int topic_in_unit(const unsigned char* slots, uint32_
 
 // Rows too long for the kept shapes, one per wave (sub-lane = lane): one walk for the sums, a
 // second one over the hit lane's entries.  Lane l owns the units [n l, n (l + 1)).
-template <class Layout>
-__device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenRec* rec, int lane) {
+template <class Layout, class Weights>
+__device__ __forceinline__ void row_pass_long(const Weights& weight_at, const unsigned char* slots, TokenRec* rec,
+                                              int lane) {
     constexpr int UE = Layout::kUnitEntries;
     const RowCtx r = row_ctx(rec);
     const int nnz = rec->nnz;
@@ -535,7 +558,8 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenR
     uint64_t prev_own = __ballot(own_before);
     double acc = 0.0;
     for (int c = 0; c < n; ++c)
-        unit_sum<Layout>(load_unit(slots, r.off, u0 + c, u0 + c < n_units), r.o_key, r.w_o, prev_own, acc);
+        unit_sum<Layout>(weight_at, load_unit(slots, r.off, u0 + c, u0 + c < n_units), r.o_key, r.w_o, prev_own,
+                         acc);
     const RowDraw d = row_draw<kWave>(acc, rec, lane, lane);
     if (__ballot(d.hit) != 0) {
         bool found = false;
@@ -546,8 +570,8 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenR
             double sums[UE];
             int keys[UE];
             const double before_unit = acc;
-            unit_prefix_sums<Layout>(load_unit(slots, r.off, u0 + c, d.hit && u0 + c < n_units), r.o_key,
-                                     r.w_o, prev_own, acc, sums, keys);
+            unit_prefix_sums<Layout>(weight_at, load_unit(slots, r.off, u0 + c, d.hit && u0 + c < n_units),
+                                     r.o_key, r.w_o, prev_own, acc, sums, keys);
 #pragma unroll
             for (int j = 0; j < UE; ++j) {
                 const double before = (j == 0) ? before_unit : sums[j - 1];
@@ -563,7 +587,10 @@ __device__ __forceinline__ void row_pass_long(const unsigned char* slots, TokenR
     record_dense(rec, lane, d);
 }
 
-template <int kWaves, class Layout>
+// kFar: K is too large for p* to fit a workgroup's LDS.  p* of the workgroup's tile then lives in
+// the workgroup's own strip of device memory (the prefix sums and the records stay in LDS), and
+// the launch has as many workgroups as there are strips, each taking every grid-th tile.
+template <int kWaves, class Layout, bool kFar = false>
 // Six waves per SIMD (80 VGPRs): the walk hides HBM latency by occupancy as well as by the
 // early loads.
 __attribute__((amdgpu_waves_per_eu(Layout::kWavesPerSimd)))
@@ -571,12 +598,16 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int kGroup = dense_group(kWaves);
     const int K = a.K, Kpad = a.Kpad, ng = Kpad / kGroup;
-    float* pstar = reinterpret_cast<float*>(lds);
-    double* cp = reinterpret_cast<double*>(lds + (size_t)Kpad * 4);
+    const size_t pstar_lds = kFar ? 0 : (size_t)Kpad * 4;
+    float* pstar = kFar ? a.far_pstar + (size_t)blockIdx.x * (size_t)Kpad : reinterpret_cast<float*>(lds);
+    double* cp = reinterpret_cast<double*>(lds + pstar_lds);
     const int tid = (int)threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);      // wave-uniform, in an SGPR
-    unsigned char* wave_base = lds + (size_t)Kpad * 4 + (size_t)((ng + 1) & ~1) * 8;
+    unsigned char* wave_base = lds + pstar_lds + (size_t)((ng + 1) & ~1) * 8;
     TokenRec* my_rec = reinterpret_cast<TokenRec*>(wave_base) + wave * kWave;
+    typedef typename std::conditional<kFar, FarWeights, LdsWeights>::type Weights;
+    Weights weight_at;
+    if constexpr (kFar) weight_at.base = reinterpret_cast<const unsigned char*>(pstar);
 
     // The workgroup's tiles: one, or (large K only) a run of small ones.  What says where the
     // run starts and ends is worked out again where it is needed rather than kept through the
@@ -584,7 +615,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     // Runs are dealt evenly among the other workgroups in launch order (the runs wait for memory
     // most of the time, the large tiles keep the arithmetic units busy: side by side on a CU they
     // fill each other's gaps): of the workgroups before b, floor(b * n_runs / grid) take a run.
-    constexpr bool kRuns = kWaves == 12;
+    constexpr bool kRuns = kWaves == 12 && !kFar;
     auto runs_before = [&](int b) {
         const int n_runs = (int)gridDim.x - a.n_single;
         return (int)((int64_t)b * n_runs / (int64_t)gridDim.x);
@@ -600,7 +631,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
     if (in_run()) {
         for (int w = tid; w < (ng + 31) / 32; w += kWaves * kWave) changed[w] = 0u;
     }
-    for (int ti = first_tile();;) {
+    for (int ti = kFar ? (int)blockIdx.x : first_tile();;) {
     Tile tl = a.tiles[ti];                 // the same for every lane: keep it in SGPRs
     tl.word = __builtin_amdgcn_readfirstlane(tl.word);
     tl.begin = __builtin_amdgcn_readfirstlane(tl.begin);
@@ -807,18 +838,18 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             shape_next = shape_at(t_req);
             request(t_req, shape_next, rec_next, sl_next, next_raw, t_next < n_here);
             switch (shape) {
-            case 0: row_pass_kept<Layout, 4, 1>(rec, sl, first_unit, mine_raw, lane); break;
-            case 1: row_pass_kept<Layout, 4, 2>(rec, sl, first_unit, mine_raw, lane); break;
-            case 2: row_pass_kept<Layout, 4, 3>(rec, sl, first_unit, mine_raw, lane); break;
-            case 3: row_pass_kept<Layout, 8, 2>(rec, sl, first_unit, mine_raw, lane); break;
-            case 4: row_pass_kept<Layout, 8, 3>(rec, sl, first_unit, mine_raw, lane); break;
-            case 5: row_pass_kept<Layout, 16, 2>(rec, sl, first_unit, mine_raw, lane); break;
-            case 6: row_pass_kept<Layout, 16, 3>(rec, sl, first_unit, mine_raw, lane); break;
-            case 7: row_pass_kept<Layout, 32, 2>(rec, sl, first_unit, mine_raw, lane); break;
-            case 8: row_pass_kept<Layout, 32, 3>(rec, sl, first_unit, mine_raw, lane); break;
-            case 9: row_pass_kept<Layout, 64, 2>(rec, sl, first_unit, mine_raw, lane); break;
-            case 10: row_pass_kept<Layout, 64, 3>(rec, sl, first_unit, mine_raw, lane); break;
-            default: row_pass_long<Layout>(a.slots, rec, lane); break;
+            case 0: row_pass_kept<Layout, 4, 1>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 1: row_pass_kept<Layout, 4, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 2: row_pass_kept<Layout, 4, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 3: row_pass_kept<Layout, 8, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 4: row_pass_kept<Layout, 8, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 5: row_pass_kept<Layout, 16, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 6: row_pass_kept<Layout, 16, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 7: row_pass_kept<Layout, 32, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 8: row_pass_kept<Layout, 32, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 9: row_pass_kept<Layout, 64, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 10: row_pass_kept<Layout, 64, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            default: row_pass_long<Layout>(weight_at, a.slots, rec, lane); break;
             }
         };
         uint4 raw_a[kKeptUnits], raw_b[kKeptUnits];
@@ -841,7 +872,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             const float w_o = __int_as_float(head.w);
             int z_new = head.x;
             if (head.y == kDrawInUnit)
-                z_new = topic_in_unit<Layout>(a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
+                z_new = topic_in_unit<Layout>(weight_at, a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
             if (head.y == kDrawDense)
                 z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, head.z, w_o,
                                                     (double)w_o - (double)pstar[head.z]);
@@ -850,8 +881,8 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
-    ti += 1;
-    if (!kRuns || ti >= last_tile()) break;
+    ti += kFar ? (int)gridDim.x : 1;
+    if (kFar ? ti >= a.n_tiles : (!kRuns || ti >= last_tile())) break;
     __syncthreads();                // every wave is done with this word's p*
     }
 }

@@ -57,8 +57,25 @@ int sample_waves_for(int32_t K) { return K <= 2048 ? 4 : 12; }
 // theta rows with 2-byte entries where the topics fit their ten bits
 bool tiny_rows_for(int32_t K) { return K <= mlda::TinyRows::kMaxK; }
 
+// What the sampler's LDS holds besides p* itself belongs to K as well: Kpad = K + 1 rounded up to
+// a multiple of the dense bucket's group (one zero entry of p* past the last topic: padding
+// entries of theta rows point at it).
+int32_t kpad_for(int32_t K) {
+    const int32_t g = mlda::dense_group(sample_waves_for(K));
+    return (K + g) / g * g;
+}
+// p* of one word beside the prefix sums and the waves' records: where that exceeds the LDS a
+// workgroup can have on this chip (K beyond about 30,900), p* lives in device memory instead,
+// one strip per workgroup of a launch of at most kFarStrips workgroups.
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;
+constexpr int kFarStrips = 512;
+bool far_weights_for(int32_t K) {
+    return mlda::sample_lds_bytes(kpad_for(K), sample_waves_for(K)) > kLdsPerWorkgroup;
+}
+
 // short_docs: no document has more tokens than a 4-byte entry counts
 const void* sample_kernel_for(int32_t K, bool short_docs) {
+    if (far_weights_for(K)) return (const void*)mlda::sample_kernel<12, mlda::PackedRows, true>;
     if (tiny_rows_for(K)) return (const void*)mlda::sample_kernel<4, mlda::TinyRows>;
     if (sample_waves_for(K) == 4)
         return short_docs ? (const void*)mlda::sample_kernel<4, mlda::PackedRowsShort>
@@ -84,6 +101,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 int tile_tokens_for(int32_t K) { return K <= 2048 ? 1024 : 4096; }
 constexpr int kPhiSegment = 16384;    // tokens one workgroup histograms for the phi rebuild
+constexpr int32_t kHistTopics = 32768; // 32-bit counters of the phi and n_k histograms that share a workgroup's LDS
 
 // A theta row's slot: a header of kRowHeader bytes (the row's number of entries), then the
 // entries, filled up to whole 16-byte units.  A document of n tokens needs at most
@@ -148,7 +166,7 @@ ChunkLayout chunk_layout_bound(int64_t D, int64_t T, int32_t V, int32_t K, bool 
 // the words with 2^16 tokens or more, of which a corpus of T tokens has at most T / 2^16.
 struct ModelLayout {
     size_t phi[2] = {0, 0}, phi_wide = 0, phi_bytes = 0, wide_row = 0, n_k[2] = {0, 0}, ll_partial = 0,
-           ll_scalars = 0, lg_table = 0, row_entries = 0, total = 0;
+           ll_scalars = 0, lg_table = 0, row_entries = 0, far_pstar = 0, total = 0;
 };
 
 int64_t wide_rows_bound(int32_t V, int64_t T) {
@@ -170,6 +188,7 @@ ModelLayout model_layout(int32_t V, int32_t K, int64_t T, bool two_phi) {
     L.ll_scalars = put(4 * 8);                            // value, theta sum, document term, spare
     L.lg_table = put((size_t)(mlda::kLgTable + 1) * 8 * 2);   // one for alpha, one for beta
     L.row_entries = put((size_t)kEntryRing * 8);
+    L.far_pstar = put(far_weights_for(K) ? (size_t)kFarStrips * (size_t)kpad_for(K) * 4 : 0);
     L.total = at;
     return L;
 }
@@ -449,6 +468,8 @@ struct mlda_ctx {
     int32_t iter = 0;
     hipStream_t stream = nullptr;
     int n_cus = 0, lds_limit = 0;
+    bool far_weights = false;           // p* of the sampler's tiles in device memory (large K)
+    float* far_pstar = nullptr;
     size_t sample_lds = 0;
     mlda::PhiView phi[2];                // [model_cur] is the current phi; two copies when streamed
     size_t phi_bytes = 0;                // bytes of one copy
@@ -687,7 +708,10 @@ int store_z_and_release(mlda_ctx* c, int32_t m, bool store) {
 // zeroed before the first chunk, and n_k is formed after the last (finish_model).
 int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
     using namespace mlda;
-    const size_t hist_bytes = (size_t)c->K * 4;
+    // one counter per topic in LDS; K beyond kHistTopics is counted range by range
+    const int32_t span = std::min<int32_t>(c->K, kHistTopics);
+    const size_t hist_bytes = (size_t)span * 4;
+    const bool ranges = c->K > kHistTopics;
     if (!c->streamed) {
         if (c->n_split > 0) {
             dim3 grid((unsigned)c->n_split, (unsigned)blocks_for(c->K, 256));
@@ -698,8 +722,13 @@ int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
                            c->n_k[which], (int64_t)c->K, 0);
     }
     if (c->n_tiles > 0) {
-        hipLaunchKernelGGL(phi_tile_kernel, dim3((unsigned)c->n_segs), dim3(256), hist_bytes, c->stream,
-                           c->segs, z, c->phi[which], c->K);
+        if (!ranges)
+            hipLaunchKernelGGL(phi_tile_kernel<false>, dim3((unsigned)c->n_segs), dim3(256), hist_bytes, c->stream,
+                               c->segs, z, c->phi[which], c->K, 0, c->K);
+        else
+            for (int32_t k_lo = 0; k_lo < c->K; k_lo += span)
+                hipLaunchKernelGGL(phi_tile_kernel<true>, dim3((unsigned)c->n_segs), dim3(256), hist_bytes,
+                                   c->stream, c->segs, z, c->phi[which], c->K, k_lo, std::min(span, c->K - k_lo));
         if (c->streamed) {
             // n_k after the last chunk
         } else if ((int64_t)c->V * c->K * 2 < c->T) {
@@ -710,8 +739,13 @@ int rebuild_phi(mlda_ctx* c, const uint16_t* z, int which) {
                                c->phi[which], c->V, c->n_wide, c->K, words_per_slice, c->n_k[which]);
         } else {
             const int grid = (int)std::min<int64_t>((c->T + 4095) / 4096, (int64_t)c->n_cus * 8);
-            hipLaunchKernelGGL(topic_totals_kernel, dim3((unsigned)grid), dim3(256), hist_bytes, c->stream,
-                               z, c->T, c->n_k[which], c->K);
+            if (!ranges)
+                hipLaunchKernelGGL(topic_totals_kernel<false>, dim3((unsigned)grid), dim3(256), hist_bytes,
+                                   c->stream, z, c->T, c->n_k[which], c->K, 0, c->K);
+            else
+                for (int32_t k_lo = 0; k_lo < c->K; k_lo += span)
+                    hipLaunchKernelGGL(topic_totals_kernel<true>, dim3((unsigned)grid), dim3(256), hist_bytes,
+                                       c->stream, z, c->T, c->n_k[which], c->K, k_lo, std::min(span, c->K - k_lo));
         }
     }
     return launch_check("phi rebuild kernels");
@@ -788,8 +822,10 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     a.n_tiles = c->n_tiles;
     a.n_single = c->run_tiles > 1 ? c->n_single : c->n_tiles;
     a.run_tiles = c->run_tiles;
+    a.far_pstar = c->far_pstar;
     const int waves = sample_waves_for(c->K);
-    const int32_t grid = a.n_single + (a.n_tiles - a.n_single + a.run_tiles - 1) / a.run_tiles;
+    const int32_t grid = c->far_weights ? std::min<int32_t>(a.n_tiles, kFarStrips)
+                                        : a.n_single + (a.n_tiles - a.n_single + a.run_tiles - 1) / a.run_tiles;
     void* kernel_args[] = {&a};
     HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs), dim3((unsigned)grid),
                             dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
@@ -905,6 +941,7 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     c->lg_table = (double*)(base + ML.lg_table);
     c->lg_table_beta = c->lg_table + (mlda::kLgTable + 1);
     c->row_entries = (unsigned long long*)(base + ML.row_entries);
+    c->far_pstar = (float*)(base + ML.far_pstar);
 
     hipLaunchKernelGGL(mlda::lg_table_kernel, dim3(blocks_for(mlda::kLgTable + 1, 256)), dim3(256), 0,
                        c->stream, c->lg_table, c->alpha);
@@ -922,16 +959,29 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
             HIP_TRY(hipFuncSetAttribute(sample_kernel_for(c->K, short_docs),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
     if ((size_t)c->K * 4 > 48 * 1024) {
-        HIP_TRY(hipFuncSetAttribute((const void*)mlda::phi_tile_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
-        HIP_TRY(hipFuncSetAttribute((const void*)mlda::topic_totals_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, c->K * 4));
+        const int hist_bytes = std::min<int32_t>(c->K, kHistTopics) * 4;
+        for (const void* kernel : {(const void*)mlda::phi_tile_kernel<false>, (const void*)mlda::phi_tile_kernel<true>,
+                                   (const void*)mlda::topic_totals_kernel<false>,
+                                   (const void*)mlda::topic_totals_kernel<true>})
+            HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, hist_bytes));
     }
     for (bool wide : {false, true})
-        if (mlda::theta_lds_bytes(c->K, wide) > 48 * 1024)
+        if (mlda::theta_lds_bytes(c->K, wide) > 48 * 1024 &&
+            mlda::theta_lds_bytes(c->K, wide) <= (size_t)c->lds_limit)      // (else see check_theta_lds)
             HIP_TRY(hipFuncSetAttribute(theta_kernel_for(tiny_rows_for(c->K), wide),
                                         hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)mlda::theta_lds_bytes(c->K, wide)));
+    return MLDA_OK;
+}
+
+// The theta rebuild keeps one counter per topic in LDS: 16-bit ones, or 32-bit ones once a
+// document of the chunk has 2^16 tokens or more; the latter fit up to K of about 39,000.
+int check_theta_lds(const mlda_ctx* c, const HostChunk& h) {
+    const size_t need = mlda::theta_lds_bytes(c->K, h.wide_counters);
+    if (need > (size_t)c->lds_limit)
+        return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " with a document of 2^16 tokens or more needs " +
+                                      std::to_string(need) + " bytes of LDS per workgroup for the theta rebuild, "
+                                      "the device allows " + std::to_string(c->lds_limit));
     return MLDA_OK;
 }
 
@@ -979,10 +1029,10 @@ int device_limits(mlda_ctx* c) {
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     HIP_TRY(hipDeviceGetAttribute(&c->lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-    // one zero entry of p* past the last topic: padding entries of theta rows point at it
-    const int32_t dense_group = mlda::dense_group(sample_waves_for(c->K));
-    c->Kpad = (c->K + dense_group) / dense_group * dense_group;
-    c->sample_lds = mlda::sample_lds_bytes(c->Kpad, sample_waves_for(c->K));
+    c->Kpad = kpad_for(c->K);
+    c->far_weights = far_weights_for(c->K);
+    c->sample_lds = c->far_weights ? mlda::sample_far_lds_bytes(c->Kpad, sample_waves_for(c->K))
+                                   : mlda::sample_lds_bytes(c->Kpad, sample_waves_for(c->K));
     if (c->sample_lds > (size_t)c->lds_limit)
         return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " needs " + std::to_string(c->sample_lds) +
                                       " bytes of LDS per workgroup, the device allows " +
@@ -993,7 +1043,7 @@ int device_limits(mlda_ctx* c) {
     c->run_tiles = 1;
     const size_t with_runs = c->sample_lds + mlda::sample_run_lds_bytes(c->Kpad, sample_waves_for(c->K));
     const size_t cu_lds = 160 * 1024;
-    if (sample_waves_for(c->K) == 12 && !c->streamed && with_runs <= (size_t)c->lds_limit &&
+    if (sample_waves_for(c->K) == 12 && !c->far_weights && !c->streamed && with_runs <= (size_t)c->lds_limit &&
         (2 * with_runs <= cu_lds || 2 * c->sample_lds > cu_lds)) {
         c->sample_lds = with_runs;
         c->run_tiles = kRunTiles;
@@ -1193,6 +1243,7 @@ static int create_resident(mlda_ctx** out, const int64_t* doc_ptr, const int32_t
         try { c->chunks = std::vector<HostChunk>(1); } catch (const std::bad_alloc&) { rc = fail(MLDA_ENOMEM, "out of host memory"); }
     }
     if (rc == MLDA_OK) rc = prepare_chunk(doc_ptr, word_ids, 0, D, V, K, false, false, c->run_tiles > 1, c->chunks[0]);
+    if (rc == MLDA_OK) rc = check_theta_lds(c, c->chunks[0]);
     if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[0]);
     const ModelLayout ML = model_layout(V, K, T, false);
     if (rc == MLDA_OK && ML.total + c->chunks[0].L.total > workspace_bytes)
@@ -1261,6 +1312,7 @@ int mlda_create_streamed(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* 
     for (int32_t m = 0; rc == MLDA_OK && m < n_chunks; ++m) {
         rc = prepare_chunk(doc_ptr, word_ids, chunk_first(doc_ptr, D, n_chunks, m),
                            chunk_first(doc_ptr, D, n_chunks, m + 1), V, K, true, true, false, c->chunks[(size_t)m]);
+        if (rc == MLDA_OK) rc = check_theta_lds(c, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) mark_wide_tiles(c, c->chunks[(size_t)m]);
         if (rc == MLDA_OK) chunk_bytes = std::max(chunk_bytes, c->chunks[(size_t)m].L.total);
     }

@@ -118,6 +118,12 @@ EDGE_CASES = [
     ("large_k_mixed_words", 400, 70,   3000, 300),
     ("k_twenty_thousand",   40,  300,  20000, 400),   # every kernel beyond 64 KB of LDS
     ("k_near_lds_limit",    40,  300,  30800, 400),   # 160 KB of LDS: one workgroup per CU
+    # K whose p* does not fit a workgroup's LDS: p* of a tile in device memory, a fixed number of
+    # workgroups that take tile after tile (1,500 words: more tiles than workgroups); beyond
+    # 32,768 topics the histograms of phi and n_k are taken in two ranges of topics
+    ("k_beyond_lds",         40,  300,  31000, 400),
+    ("k_beyond_lds_many_words", 200, 1500, 33000, 40),
+    ("k_largest",            30,  200,  65535, 300),
     # long documents over few topics: counts far beyond one entry's field are spread over
     # several entries of the same topic (2-byte entries hold counts up to 15)
     ("huge_docs_split_rows", 3,   400,  700, 17000),
@@ -256,6 +262,20 @@ def test_streamed_chunks_match_oracle(mlda, chunks):
     ms, moved = model.timing(), model.sampler_bytes()      # per iteration, summed over the chunks
     assert ms.shape == (2, 4) and np.all(ms > 0) and moved.shape == (2,)
     assert np.all(moved >= 16.0 * c.T)
+    model.close()
+
+
+def test_streamed_with_weights_in_device_memory(mlda):
+    """K beyond the LDS column, the corpus in three chunks: p* in device memory, phi counted in
+    two ranges of topics and added to chunk by chunk."""
+    D, V, K = 30, 100, 33000
+    c = corpus_synth.tiny(D=D, V=V, K=K, mean_len=100, seed=8, name="far_streamed")
+    alpha, beta = 50.0 / K, 0.01
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, SEED, chunks=3)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, SEED)
+    for it in (1, 2):
+        z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
     model.close()
 
 
@@ -467,10 +487,17 @@ def test_device_side_argument_errors(mlda):
     rc = lib.mlda_create(ctypes.addressof(ctx), c.doc_ptr.ctypes.data, c.word_ids.ctypes.data,
                          10, 20, 4, 0.5, 0.01, 1, ctypes.c_void_p(addr), (1 << 22) - 256, None)
     assert rc == -1 and b"not device memory" in lib.mlda_last_error()
-    # K whose p* column cannot fit in LDS
+    # the one combination beyond the device's LDS: 32-bit counters per topic in the theta rebuild
+    # (a document of 2^16 tokens or more) with K beyond about 39,000
     big_k = 60000
-    need = mlda.workspace_bytes(10, c.T, 20, big_k)
+    lens = np.array([5, 65536, 3], dtype=np.int64)
+    long_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    long_words = (np.arange(long_ptr[-1]) % 20).astype(np.int32)
+    need = mlda.workspace_bytes(3, int(long_ptr[-1]), 20, big_k)
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-    rc = lib.mlda_create(ctypes.addressof(ctx), c.doc_ptr.ctypes.data, c.word_ids.ctypes.data,
-                         10, 20, big_k, 0.5, 0.01, 1, ws.data_ptr(), need, None)
+    rc = lib.mlda_create(ctypes.addressof(ctx), long_ptr.ctypes.data, long_words.ctypes.data,
+                         3, 20, big_k, 0.5, 0.01, 1, ws.data_ptr(), need, None)
     assert rc == -4 and b"LDS" in lib.mlda_last_error()
+    # the same K with shorter documents is served
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, 20, big_k, 0.5, 0.01, 1)
+    model.close()
