@@ -47,6 +47,15 @@ def test_workspace_bytes_validates_and_bounds(lib):
         assert lib.mlda_workspace_bytes(D, T, V, K, ctypes.addressof(n)) == -1
     assert lib.mlda_workspace_bytes(1, 10, 5, 4, None) == -1
     assert b"null" in lib.mlda_last_error()
+    # a K whose column of p* does not fit the LDS of a workgroup: the workspace also holds the
+    # 512 columns of p* that the sampler's workgroups then keep in device memory
+    sizes = {}
+    for K in (30_000, 31_000, 65_535):
+        assert lib.mlda_workspace_bytes(10, 1000, 5, K, ctypes.addressof(n)) == 0
+        sizes[K] = n.value
+    assert sizes[30_000] < 8 * 1024 * 1024
+    assert sizes[31_000] - sizes[30_000] >= 512 * 31_000 * 4
+    assert sizes[65_535] >= 512 * 65_536 * 4
 
 
 def test_create_rejects_bad_arguments_on_the_host(lib):
