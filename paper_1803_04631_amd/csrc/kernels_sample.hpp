@@ -7,6 +7,9 @@
 //   - a workgroup owns one tile = up to 1024 (4096 for large K) consecutive tokens of ONE
 //     word and stages that word's p*(k) (Eq. 8) once in LDS as fp32, with fp64 prefix sums
 //     over groups of 4 (or 16) topics (Section 6.1.2: samplers of a block share the word's data);
+//     for large K, the many words of few tokens are taken in runs by one workgroup, which turns
+//     p* of one word into p* of the next; where K is too large for p* to fit the LDS at all, it
+//     is staged in a strip of device memory that the workgroup owns, and read from there;
 //   - each wave takes 64 tokens at a time (fewer when a large-K tile is too small to give every
 //     wave that many).  What is per token and needs no cooperation is
 //     done one token per LANE: the Philox uniform, the token's own-count correction of
