@@ -56,13 +56,12 @@ extern "C" {
                               2^31 or more tokens, topic >= K) */
 #define MLDA_ENOMEM   -2   /* device workspace smaller than mlda_workspace_bytes, or host malloc failed */
 #define MLDA_EHIP     -3   /* a HIP call failed; the message names it */
-#define MLDA_ENOTSUP  -4   /* the one combination that exceeds the 160 KB of LDS a workgroup may use: K beyond
-                              about 39,000 together with a document of 2^16 tokens or more (the theta
-                              rebuild then needs a 32-bit counter per topic in LDS).  Every other K up to
-                              65,535, the range of the 16-bit topic index (Section 6.1.3), is served: up to
-                              about 30,900 the sampler keeps the word's column of p* (Eq. 8) in LDS, beyond
-                              that in device memory, several times slower; the paper's own range is 1,000
-                              to 10,000 (Section 2.1) */
+#define MLDA_ENOTSUP  -4   /* the device allows a workgroup less LDS than a kernel needs for this K (not on
+                              MI355X, whose 160 KB serve every K up to 65,535, the range of the 16-bit topic
+                              index of Section 6.1.3: up to about 30,900 the sampler keeps the word's column
+                              of p* (Eq. 8) in LDS, beyond that in device memory, several times slower; the
+                              paper's own range is 1,000 to 10,000, Section 2.1); also theta rows beyond
+                              64 GiB in one chunk, and a device index beyond the library's table */
 
 #define MLDA_STEP_LOGLIK 1u /* mlda_step flag: also evaluate the log-likelihood after each iteration */
 
@@ -85,9 +84,7 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
  * topics are assigned yet: call mlda_init_random or mlda_set_assignments next.
  * K: 1 .. 65,535 (MLDA_EINVAL outside).  A K whose column of p* does not fit the 160 KB of LDS
  * of a workgroup (beyond about 30,900) is sampled with p* in device memory: same results, several
- * times slower per token; the workspace then holds 512 such columns more.  MLDA_ENOTSUP only for
- * K beyond about 39,000 with a document of 2^16 tokens or more; the message names the bytes
- * needed and allowed.
+ * times slower per token; the workspace then holds 512 such columns more.
  */
 int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                 int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,

@@ -199,12 +199,18 @@ __device__ __forceinline__ int doc_token_topic(const uint16_t* z, int position, 
 // LDS bytes of the rebuild's dense row: the counters (two 16-bit counters per dword, or one
 // 32-bit counter per topic when some document has 2^16 tokens or more), then one bit per topic
 // that marks the non-zero bins.
+// (32-bit counters for more than kThetaWideSpan topics would not fit the LDS: such a document is
+// counted once per range of that many topics, and its row grows range by range.)
+constexpr int32_t kThetaWideSpan = 32768;
+__host__ __device__ inline int32_t theta_span(int32_t K, bool wide) {
+    return wide && K > kThetaWideSpan ? kThetaWideSpan : K;
+}
 __host__ __device__ inline size_t theta_counter_bytes(int32_t K, bool wide) {
-    const size_t counters = wide ? (size_t)K * 4 : (size_t)((K + 1) / 2) * 4;
+    const size_t counters = wide ? (size_t)theta_span(K, wide) * 4 : (size_t)((K + 1) / 2) * 4;
     return (counters + 15) & ~(size_t)15;
 }
 __host__ __device__ inline size_t theta_hist_bytes(int32_t K, bool wide) {
-    const size_t marks = (size_t)((K + 31) / 32) * 4;
+    const size_t marks = (size_t)((theta_span(K, wide) + 31) / 32) * 4;
     return theta_counter_bytes(K, wide) + ((marks + 15) & ~(size_t)15);
 }
 __host__ __device__ inline size_t theta_lds_bytes(int32_t K, bool wide) {
@@ -273,8 +279,9 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
     }
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
-    const int n_counters = kWide ? K : (K + 1) / 2;
-    const int n_marks = (K + 31) / 32;
+    const int span = theta_span(K, kWide);       // topics counted at a time: all, but for kWide and a very large K
+    const int n_counters = kWide ? span : (K + 1) / 2;
+    const int n_marks = (span + 31) / 32;
     uint32_t* marks = reinterpret_cast<uint32_t*>(lds + theta_counter_bytes(K, kWide));
     double* table = reinterpret_cast<double*>(lds + theta_hist_bytes(K, kWide));
     const int lane = (int)threadIdx.x;
@@ -343,10 +350,20 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
         const int q1 = doc_token_position_any(doc_map, after, lane + kWave);
         const DocRec later = record(i + 3 * step);
 
-        bool outgrown = false;
         const bool long_doc = cur.n > Layout::kMaxCount;     // (the same for the whole wave)
+        unsigned char* head = slots + (size_t)cur.slot * 16u;
+        Entry* ent = reinterpret_cast<Entry*>(head + kRowHeader);
+        int filled = 0, distinct = 0;
+        bool any_split = false;
+        // (one round, but for 32-bit counters and more topics than they have room for)
+        for (int k_lo = 0; k_lo < K; k_lo += span) {
+        bool outgrown = false;
         auto count = [&](int k) {
             if (k < 0) return;
+            if (kWide) {
+                k -= k_lo;
+                if ((unsigned)k >= (unsigned)span) return;
+            }
             if (long_doc) outgrown |= count_topic(k); else count_topic_short(k);
         };
         count(k0);
@@ -363,13 +380,11 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
             for (int t = 0; t < 4; ++t) count(k[t]);
         }
         __syncthreads();
-        unsigned char* head = slots + (size_t)cur.slot * 16u;
-        Entry* ent = reinterpret_cast<Entry*>(head + kRowHeader);
         // some count of the document takes several entries
         const bool may_split = __ballot(outgrown) != 0;
+        any_split |= may_split;
         // Each lane owns one word of marks (32 topics) per round and writes its non-zero bins
         // in ascending order behind those of the lanes below it.
-        int filled = 0, distinct = 0;
         for (int base = 0; base < n_marks; base += kWave) {
             const int wi = base + lane;
             uint32_t w = wi < n_marks ? marks[wi] : 0u;
@@ -393,7 +408,7 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                         w &= w - 1u;
                         c = (int)hist[k];
                         hist[k] = 0u;
-                        at = write_entries<Layout>(ent, at, k, c);
+                        at = write_entries<Layout>(ent, at, k_lo + k, c);
                     }
                     add_ll(c);
                 }
@@ -416,8 +431,10 @@ __global__ __launch_bounds__(kWave) void theta_rows_kernel(const DocRec* docs,
                 }
             }
         }
+        if (k_lo + span < K) __syncthreads();
+        }
         close_row<Layout>(head, filled, K, lane, true);
-        const int nnz = may_split ? wave_sum(distinct) : filled;
+        const int nnz = any_split ? wave_sum(distinct) : filled;
         if (lane == 0) row_rec[cur.doc].y = (uint32_t)nnz;      // distinct topics, for the getters
         visited += (unsigned long long)cur.n * (unsigned long long)filled;
         __syncthreads();

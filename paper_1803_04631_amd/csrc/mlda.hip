@@ -974,14 +974,15 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     return MLDA_OK;
 }
 
-// The theta rebuild keeps one counter per topic in LDS: 16-bit ones, or 32-bit ones once a
-// document of the chunk has 2^16 tokens or more; the latter fit up to K of about 39,000.
+// The theta rebuild keeps counters per topic in LDS: 16-bit ones for all topics, or, once a
+// document of the chunk has 2^16 tokens or more, 32-bit ones for up to 32,768 topics at a time.
+// On a device that allows a workgroup the 160 KB this library is written for they always fit.
 int check_theta_lds(const mlda_ctx* c, const HostChunk& h) {
     const size_t need = mlda::theta_lds_bytes(c->K, h.wide_counters);
     if (need > (size_t)c->lds_limit)
-        return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " with a document of 2^16 tokens or more needs " +
-                                      std::to_string(need) + " bytes of LDS per workgroup for the theta rebuild, "
-                                      "the device allows " + std::to_string(c->lds_limit));
+        return fail(MLDA_ENOTSUP, "K = " + std::to_string(c->K) + " needs " + std::to_string(need) +
+                                      " bytes of LDS per workgroup for the theta rebuild, the device allows " +
+                                      std::to_string(c->lds_limit));
     return MLDA_OK;
 }
 
@@ -1180,7 +1181,7 @@ const char* mlda_strerror(int code) {
         case MLDA_EINVAL: return "invalid argument";
         case MLDA_ENOMEM: return "workspace too small or out of host memory";
         case MLDA_EHIP: return "HIP call failed";
-        case MLDA_ENOTSUP: return "K too large for the device's LDS";
+        case MLDA_ENOTSUP: return "beyond what the device or the library supports";
         default: return "unknown error";
     }
 }

@@ -151,6 +151,34 @@ def test_edge_shapes(mlda, case):
     model.close()
 
 
+def test_long_document_with_more_topics_than_32bit_counters_fit(mlda):
+    """A document of 2^16 tokens or more needs 32-bit counters in the theta rebuild; beyond
+    32,768 topics they do not fit the LDS at once and the document is counted in two ranges of
+    topics, its row growing range by range.  Counts beyond one entry's 16,383 in both ranges."""
+    V, K = 50, 40000
+    lens = np.array([70000, 300, 5, 0, 66000], dtype=np.int64)
+    doc_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rng = np.random.default_rng(5)
+    words = rng.integers(V, size=int(lens.sum())).astype(np.int32)
+    z = rng.integers(K, size=len(words)).astype(np.uint16)
+    z[0:20000] = 7                              # 20,000 tokens of a topic of the first range
+    z[20000:38000] = 32767                      # the last topic of the first range
+    z[38000:56000] = 32768                      # the first topic of the second
+    z[56000:60000] = K - 1
+    z[doc_ptr[4]:doc_ptr[4] + 40000] = 39000    # the last document: mostly one topic of the second range
+
+    class C:  # minimal corpus record
+        pass
+    c = C(); c.doc_ptr = doc_ptr; c.word_ids = words; c.T = len(words)
+    alpha, beta = 50.0 / K, 0.01
+    model = mlda.Mlda(doc_ptr, words, V, K, alpha, beta, SEED)
+    model.set_assignments(z, it=0)
+    assert np.array_equal(model.assignments(), z)
+    check_counts(model, c, z, V, K)
+    check_step(model, c, z, V, K, alpha, beta, SEED, 1)
+    model.close()
+
+
 @pytest.mark.parametrize("K", [500, 1500])
 def test_counts_beyond_one_entry(mlda, K):
     """Documents whose tokens sit in one or two topics: counts of 20,000 to 70,000, which no entry
@@ -487,17 +515,7 @@ def test_device_side_argument_errors(mlda):
     rc = lib.mlda_create(ctypes.addressof(ctx), c.doc_ptr.ctypes.data, c.word_ids.ctypes.data,
                          10, 20, 4, 0.5, 0.01, 1, ctypes.c_void_p(addr), (1 << 22) - 256, None)
     assert rc == -1 and b"not device memory" in lib.mlda_last_error()
-    # the one combination beyond the device's LDS: 32-bit counters per topic in the theta rebuild
-    # (a document of 2^16 tokens or more) with K beyond about 39,000
+    # every K up to 65,535 is served
     big_k = 60000
-    lens = np.array([5, 65536, 3], dtype=np.int64)
-    long_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
-    long_words = (np.arange(long_ptr[-1]) % 20).astype(np.int32)
-    need = mlda.workspace_bytes(3, int(long_ptr[-1]), 20, big_k)
-    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-    rc = lib.mlda_create(ctypes.addressof(ctx), long_ptr.ctypes.data, long_words.ctypes.data,
-                         3, 20, big_k, 0.5, 0.01, 1, ws.data_ptr(), need, None)
-    assert rc == -4 and b"LDS" in lib.mlda_last_error()
-    # the same K with shorter documents is served
     model = mlda.Mlda(c.doc_ptr, c.word_ids, 20, big_k, 0.5, 0.01, 1)
     model.close()
