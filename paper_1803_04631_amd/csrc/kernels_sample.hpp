@@ -292,6 +292,15 @@ __device__ __forceinline__ uint4 load_unit(const unsigned char* slots, uint32_t 
     return *reinterpret_cast<const uint4*>(slots + (size_t)at * 16u);
 }
 
+// The same for a slot buffer smaller than 4 GiB.  `row_bytes` is the byte offset of the lane's
+// first unit, `c` (a constant) the unit's number among the lane's units; a lane without that
+// unit reads padding unit c (the buffer starts with kKeptUnits + 1 of them).
+__device__ __forceinline__ uint4 load_unit_near(const unsigned char* slots, uint32_t row_bytes, int c, bool on) {
+    uint32_t at = on ? row_bytes : 0u;
+    asm volatile("" : "+v"(at));
+    return *reinterpret_cast<const uint4*>(slots + (size_t)at + (size_t)(c * 16));
+}
+
 // Key of the entry that lies just before a unit in memory (a row's header ends in a padding
 // entry, so this is always an entry).
 template <class Layout>
@@ -593,7 +602,9 @@ __device__ __forceinline__ void row_pass_long(const Weights& weight_at, const un
 // kFar: K is too large for p* to fit a workgroup's LDS.  p* of the workgroup's tile then lives in
 // the workgroup's own strip of device memory (the prefix sums and the records stay in LDS), and
 // the launch has as many workgroups as there are strips, each taking every grid-th tile.
-template <int kWaves, class Layout, bool kFar = false>
+// kNear: every byte of the slot buffer has a 32-bit offset; a pass then finds its units with
+// 32-bit arithmetic (one offset per lane, the unit's place in the load's own offset field).
+template <int kWaves, class Layout, bool kFar = false, bool kNear = false>
 // Six waves per SIMD (80 VGPRs): the walk hides HBM latency by occupancy as well as by the
 // early loads.
 __attribute__((amdgpu_waves_per_eu(Layout::kWavesPerSimd)))
@@ -819,10 +830,17 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             // units the lane loads: those of the shape that the row still has from its first on
-            const int n_mine = live ? min((((int)where.y + UE - 1) / UE) - geo_q0, nu) : 0;
+            const int n_mine = live ? min((int)((where.y + (uint32_t)(UE - 1)) / (uint32_t)UE) - geo_q0, nu) : 0;
+            if constexpr (kNear) {
+                const uint32_t row_bytes = (where.x + 1u + (uint32_t)geo_q0) << 4;
 #pragma unroll
-            for (int c = 0; c < kKeptUnits; ++c)
-                raw[c] = load_unit(a.slots, where.x, geo_q0 + c, c < n_mine);
+                for (int c = 0; c < kKeptUnits; ++c)
+                    raw[c] = load_unit_near(a.slots, row_bytes, c, c < n_mine);
+            } else {
+#pragma unroll
+                for (int c = 0; c < kKeptUnits; ++c)
+                    raw[c] = load_unit(a.slots, where.x, geo_q0 + c, c < n_mine);
+            }
         };
         int t_next = 0, shape_next = shape_at(0), sl_next;
         TokenRec* rec_next;

@@ -73,16 +73,22 @@ bool far_weights_for(int32_t K) {
     return mlda::sample_lds_bytes(kpad_for(K), sample_waves_for(K)) > kLdsPerWorkgroup;
 }
 
-// short_docs: no document has more tokens than a 4-byte entry counts
-const void* sample_kernel_for(int32_t K, bool short_docs) {
-    if (far_weights_for(K)) return (const void*)mlda::sample_kernel<12, mlda::PackedRows, true>;
-    if (tiny_rows_for(K)) return (const void*)mlda::sample_kernel<4, mlda::TinyRows>;
+// short_docs: no document has more tokens than a 4-byte entry counts; near: the theta slots of
+// the chunk end below 4 GiB, so that 32-bit byte offsets reach them
+template <bool kNear>
+const void* sample_kernel_of(int32_t K, bool short_docs) {
+    if (far_weights_for(K)) return (const void*)mlda::sample_kernel<12, mlda::PackedRows, true, kNear>;
+    if (tiny_rows_for(K)) return (const void*)mlda::sample_kernel<4, mlda::TinyRows, false, kNear>;
     if (sample_waves_for(K) == 4)
-        return short_docs ? (const void*)mlda::sample_kernel<4, mlda::PackedRowsShort>
-                          : (const void*)mlda::sample_kernel<4, mlda::PackedRows>;
-    return short_docs ? (const void*)mlda::sample_kernel<12, mlda::PackedRowsShort>
-                      : (const void*)mlda::sample_kernel<12, mlda::PackedRows>;
+        return short_docs ? (const void*)mlda::sample_kernel<4, mlda::PackedRowsShort, false, kNear>
+                          : (const void*)mlda::sample_kernel<4, mlda::PackedRows, false, kNear>;
+    return short_docs ? (const void*)mlda::sample_kernel<12, mlda::PackedRowsShort, false, kNear>
+                      : (const void*)mlda::sample_kernel<12, mlda::PackedRows, false, kNear>;
 }
+const void* sample_kernel_for(int32_t K, bool short_docs, bool near) {
+    return near ? sample_kernel_of<true>(K, short_docs) : sample_kernel_of<false>(K, short_docs);
+}
+bool slots_near(size_t slots_bytes) { return slots_bytes <= 0xffffffffull; }
 const void* theta_kernel_for(bool tiny, bool wide_counters) {
     if (tiny) return wide_counters ? (const void*)mlda::theta_rows_kernel<mlda::TinyRows, true>
                                    : (const void*)mlda::theta_rows_kernel<mlda::TinyRows, false>;
@@ -290,7 +296,7 @@ int prepare_chunk(const int64_t* doc_ptr_all, const int32_t* word_ids_all, int64
             order_tokens[(size_t)i + 1] = order_tokens[(size_t)i] + len_of(doc_order[(size_t)i]);
         // theta row slots: fixed capacity, so rows never move; laid out in the
         // order the documents are worked on, so that rows in use together are neighbours.
-        // The buffer starts with four padding entries.
+        // The buffer starts with 64 bytes of padding entries.
         slot_of.resize((size_t)D);
         h.slots_bytes = kSlotAlign;
         for (int64_t i = 0; i < D; ++i) {
@@ -617,8 +623,8 @@ void point_at(mlda_ctx* c, const HostChunk& h, unsigned char* base) {
 
 // After the static part of a chunk has arrived: the index arrays that follow from it
 // (document->token map, slot of every token's theta row), and what a lane of the sampler
-// reads when it has no entries of its own: four padding entries (count 0, topic K) at the
-// start of the slot buffer.  A streamed chunk arrives with its assignments in document order
+// reads when it has no entries of its own: padding entries (count 0, topic K) in the 64 bytes
+// before the first slot.  A streamed chunk arrives with its assignments in document order
 // and hands them back so: its theta rebuilds read them directly and it needs no map (building
 // one costs as much as a theta rebuild); the tokens' slots are then found by bisection.
 void derive_chunk_arrays(mlda_ctx* c) {
@@ -636,8 +642,9 @@ void derive_chunk_arrays(mlda_ctx* c) {
     }
     const uint32_t pad = c->tiny ? (uint32_t)mlda::TinyRows::make(0, c->K) * 0x10001u
                                  : (uint32_t)mlda::PackedRows::make(0, c->K);
+    static_assert(kSlotAlign >= (mlda::kKeptUnits + 1) * 16, "the padding units lie before the first slot");
     hipLaunchKernelGGL(mlda::fill_i32_kernel, dim3(1), dim3(256), 0, c->stream, (int32_t*)c->slots,
-                       (int64_t)4, (int32_t)pad);
+                       (int64_t)(kSlotAlign / 4), (int32_t)pad);
 }
 
 // Streamed: bring chunk m into the slot of this visit.  The static part (and with_z: the
@@ -827,7 +834,7 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     const int32_t grid = c->far_weights ? std::min<int32_t>(a.n_tiles, kFarStrips)
                                         : a.n_single + (a.n_tiles - a.n_single + a.run_tiles - 1) / a.run_tiles;
     void* kernel_args[] = {&a};
-    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs), dim3((unsigned)grid),
+    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs, slots_near(c->slots_bytes)), dim3((unsigned)grid),
                             dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
     return launch_check("sample_kernel");
 }
@@ -954,10 +961,11 @@ int finish_create(mlda_ctx* c, unsigned char* base, const ModelLayout& ML) {
     RC_TRY(launch_check("model set-up kernels"));
     if (c->sample_lds > 48 * 1024)
         for (bool short_docs : {false, true})
-            // (the attribute belongs to the kernel, not to this context: contexts of different
-            // needs may live side by side, so it is raised to what the device allows)
-            HIP_TRY(hipFuncSetAttribute(sample_kernel_for(c->K, short_docs),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
+            for (bool near : {false, true})
+                // (the attribute belongs to the kernel, not to this context: contexts of different
+                // needs may live side by side, so it is raised to what the device allows)
+                HIP_TRY(hipFuncSetAttribute(sample_kernel_for(c->K, short_docs, near),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
     if ((size_t)c->K * 4 > 48 * 1024) {
         const int hist_bytes = std::min<int32_t>(c->K, kHistTopics) * 4;
         for (const void* kernel : {(const void*)mlda::phi_tile_kernel<false>, (const void*)mlda::phi_tile_kernel<true>,
