@@ -757,24 +757,33 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         TokenRec mine;
         mine.off = 0; mine.nnz = 0; mine.o = 0; mine.w_o = 0.f; mine.u = 0.0; mine.Qp = 0.0;
         double delta = 0.0;
+        // What the per-token phases read of the kernel's arguments is fetched from the argument
+        // block again in every batch (scalar loads) instead of being kept in scalar registers
+        // through the passes: there are not enough of those, and what does not fit is parked in
+        // lanes of a vector register, every read of which takes a vector issue slot.
+        typedef __attribute__((address_space(4))) const SampleArgs* ArgsPtr;
+        ArgsPtr ka = (ArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(ka));
         if (valid) {
-            mine.off = a.tok_slot[pos];
-            mine.o = (int)a.z_cur[pos];
-            const uint64_t id = (uint64_t)(uint32_t)a.tok_id[pos];
+            mine.off = ka->tok_slot[pos];
+            mine.o = (int)ka->z_cur[pos];
+            const uint64_t id = (uint64_t)(uint32_t)ka->tok_id[pos];
             // the row's length sits in front of its entries: this read also brings the row's
             // first line on its way
             mine.nnz = *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
-            mine.u = token_uniform(a.seed, a.iter, id);
+            // (the seed too: the ten rounds' keys are then made where they are used, by the scalar
+            // unit, and not once per kernel)
+            mine.u = token_uniform(ka->seed, ka->iter, id);
             // the token itself is taken out of phi and n_k at its own topic
             // (its cell of phi, of either width, is cut out of the aligned dword that holds it)
             const size_t own_byte = (phi_cell0 + (size_t)mine.o) << phi_shift;
             const uint32_t own_dword = *reinterpret_cast<const uint32_t*>(phi_cells + (own_byte & ~(size_t)3));
             const int32_t phi_own = (int32_t)((own_dword >> (((uint32_t)own_byte & 2u) << 3)) & phi_mask);
-            mine.w_o = (float)(((double)(phi_own - 1) + a.beta) /
-                               ((double)(a.n_k[mine.o] - 1) + a.beta_V));
+            mine.w_o = (float)(((double)(phi_own - 1) + ka->beta) /
+                               ((double)(ka->n_k[mine.o] - 1) + ka->beta_V));
             delta = (double)mine.w_o - (double)pstar[mine.o];
             // cp[ng - 1] = sum_k p*(k), read from LDS where it is needed; Q = alpha sum (Eq. 7)
-            mine.Qp = a.alpha * (cp[ng - 1] + delta);
+            mine.Qp = ka->alpha * (cp[ng - 1] + delta);
         }
         my_rec[lane] = mine;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -895,9 +904,9 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             if (head.y == kDrawInUnit)
                 z_new = topic_in_unit<Layout>(weight_at, a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
             if (head.y == kDrawDense)
-                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, a.alpha, rec->u, head.z, w_o,
+                z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, ka->alpha, rec->u, head.z, w_o,
                                                     (double)w_o - (double)pstar[head.z]);
-            a.z_next[tl.begin + b * batch + lane] = (uint16_t)z_new;
+            ka->z_next[tl.begin + b * batch + lane] = (uint16_t)z_new;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
