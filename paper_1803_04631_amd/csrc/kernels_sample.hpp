@@ -301,6 +301,17 @@ __device__ __forceinline__ uint4 load_unit_near(const unsigned char* slots, uint
     return *reinterpret_cast<const uint4*>(slots + (size_t)at + (size_t)(c * 16));
 }
 
+// A load and a store at a 32-bit byte offset from a base that is the same for the whole wave:
+// the base stays in scalar registers and the offset is all a lane computes.
+template <class T>
+__device__ __forceinline__ T load_at(const void* base, uint32_t byte_offset) {
+    return *reinterpret_cast<const T*>(reinterpret_cast<const unsigned char*>(base) + byte_offset);
+}
+template <class T>
+__device__ __forceinline__ void store_at(void* base, uint32_t byte_offset, T v) {
+    *reinterpret_cast<T*>(reinterpret_cast<unsigned char*>(base) + byte_offset) = v;
+}
+
 // Key of the entry that lies just before a unit in memory (a row's header ends in a padding
 // entry, so this is always an entry).
 template <class Layout>
@@ -427,8 +438,8 @@ __device__ __forceinline__ void record_dense(TokenRec* rec, int sl, const RowDra
     }
 }
 
-// Rows whose sub-lanes own at most kUnits units, already loaded (`first_unit`: the lane's first
-// unit inside the row).  Every lane keeps its sum at the end of each unit; the lane that holds
+// Rows whose sub-lanes own at most kUnits units, already loaded (sub-lane sl owns the units from
+// sl * kUnits on).  Every lane keeps its sum at the end of each unit; the lane that holds
 // the draw records which unit holds it and the rest of the draw there.
 // Rows with one entry per topic, already loaded: every lane keeps the running sum after each of
 // its entries, and the lane that holds the draw finds its entry at once.
@@ -480,8 +491,9 @@ __device__ __forceinline__ void row_pass_searched(const Weights& weight_at, Toke
 }
 
 template <class Layout, int kLanes, int kUnits, class Weights>
-__device__ __forceinline__ void row_pass_kept(const Weights& weight_at, TokenRec* rec, int sl, int first_unit,
+__device__ __forceinline__ void row_pass_kept(const Weights& weight_at, TokenRec* rec, int sl,
                                               const uint4* raw, int lane) {
+    const int first_unit = sl * kUnits;
     if constexpr (Layout::kOneEntryPerTopic) {
         row_pass_searched<Layout, kLanes, kUnits>(weight_at, rec, sl, raw, lane);
         return;
@@ -529,11 +541,11 @@ __device__ __forceinline__ void row_pass_kept(const Weights& weight_at, TokenRec
 
 // The entry of one unit that holds the draw y (measured from the unit's start): the first
 // whose running sum exceeds y, else (rounding) the last one with weight.  One token per lane.
-template <class Layout, class Weights>
+template <class Layout, bool kNear, class Weights>
 __device__ __forceinline__ int topic_in_unit(const Weights& weight_at, const unsigned char* slots, uint32_t unit,
                                              int o_key, float w_o, double y) {
     constexpr int n = Layout::kUnitEntries;
-    const unsigned char* p = slots + (size_t)unit * 16u;
+    const unsigned char* p = kNear ? slots + (size_t)(uint32_t)(unit << 4) : slots + (size_t)unit * 16u;
     const uint4 raw = *reinterpret_cast<const uint4*>(p);
     uint64_t prev_own = __ballot(key_before_unit<Layout>(p) == o_key);
     double acc = 0.0;
@@ -753,7 +765,6 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // ---- one token per lane: token, uniform, own-count correction
         const int idx = b * batch + lane;
         const bool valid = lane < batch && idx < tl.count;
-        const int pos = tl.begin + idx;
         TokenRec mine;
         mine.off = 0; mine.nnz = 0; mine.o = 0; mine.w_o = 0.f; mine.u = 0.0; mine.Qp = 0.0;
         double delta = 0.0;
@@ -765,20 +776,23 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         ArgsPtr ka = (ArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
         asm volatile("" : "+s"(ka));
         if (valid) {
-            mine.off = ka->tok_slot[pos];
-            mine.o = (int)ka->z_cur[pos];
-            const uint64_t id = (uint64_t)(uint32_t)ka->tok_id[pos];
+            // (the tile's part of every per-token array starts at a scalar base)
+            mine.off = load_at<uint32_t>(ka->tok_slot + tl.begin, (uint32_t)idx << 2);
+            mine.o = (int)load_at<uint16_t>(ka->z_cur + tl.begin, (uint32_t)idx << 1);
+            const uint64_t id = (uint64_t)load_at<uint32_t>(ka->tok_id + tl.begin, (uint32_t)idx << 2);
             // the row's length sits in front of its entries: this read also brings the row's
             // first line on its way
-            mine.nnz = *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
+            mine.nnz = kNear ? load_at<int32_t>(a.slots, mine.off << 4)
+                             : *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
             // (the seed too: the ten rounds' keys are then made where they are used, by the scalar
             // unit, and not once per kernel)
             mine.u = token_uniform(ka->seed, ka->iter, id);
             // the token itself is taken out of phi and n_k at its own topic
             // (its cell of phi, of either width, is cut out of the aligned dword that holds it)
-            const size_t own_byte = (phi_cell0 + (size_t)mine.o) << phi_shift;
-            const uint32_t own_dword = *reinterpret_cast<const uint32_t*>(phi_cells + (own_byte & ~(size_t)3));
-            const int32_t phi_own = (int32_t)((own_dword >> (((uint32_t)own_byte & 2u) << 3)) & phi_mask);
+            const size_t row_byte = phi_cell0 << phi_shift;        // the word's row: scalar
+            const uint32_t own_byte = ((uint32_t)row_byte & 3u) + ((uint32_t)mine.o << phi_shift);
+            const uint32_t own_dword = load_at<uint32_t>(phi_cells + (row_byte & ~(size_t)3), own_byte & ~3u);
+            const int32_t phi_own = (int32_t)((own_dword >> ((own_byte & 2u) << 3)) & phi_mask);
             mine.w_o = (float)(((double)(phi_own - 1) + ka->beta) /
                                ((double)(ka->n_k[mine.o] - 1) + ka->beta_V));
             delta = (double)mine.w_o - (double)pstar[mine.o];
@@ -857,7 +871,6 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // go to `next_raw`.  The two buffers swap roles from pass to pass.
         auto pass = [&](uint4* mine_raw, uint4* next_raw) {
             const int shape = shape_next, sl = sl_next;
-            const int first_unit = sl * units_of(shape);
             TokenRec* rec = rec_next;
             t_next += kWave >> lanes_log2(shape);
             // The request is made whether or not a pass follows (after the batch's last pass
@@ -868,17 +881,17 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             shape_next = shape_at(t_req);
             request(t_req, shape_next, rec_next, sl_next, next_raw, t_next < n_here);
             switch (shape) {
-            case 0: row_pass_kept<Layout, 4, 1>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 1: row_pass_kept<Layout, 4, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 2: row_pass_kept<Layout, 4, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 3: row_pass_kept<Layout, 8, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 4: row_pass_kept<Layout, 8, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 5: row_pass_kept<Layout, 16, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 6: row_pass_kept<Layout, 16, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 7: row_pass_kept<Layout, 32, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 8: row_pass_kept<Layout, 32, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 9: row_pass_kept<Layout, 64, 2>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
-            case 10: row_pass_kept<Layout, 64, 3>(weight_at, rec, sl, first_unit, mine_raw, lane); break;
+            case 0: row_pass_kept<Layout, 4, 1>(weight_at, rec, sl, mine_raw, lane); break;
+            case 1: row_pass_kept<Layout, 4, 2>(weight_at, rec, sl, mine_raw, lane); break;
+            case 2: row_pass_kept<Layout, 4, 3>(weight_at, rec, sl, mine_raw, lane); break;
+            case 3: row_pass_kept<Layout, 8, 2>(weight_at, rec, sl, mine_raw, lane); break;
+            case 4: row_pass_kept<Layout, 8, 3>(weight_at, rec, sl, mine_raw, lane); break;
+            case 5: row_pass_kept<Layout, 16, 2>(weight_at, rec, sl, mine_raw, lane); break;
+            case 6: row_pass_kept<Layout, 16, 3>(weight_at, rec, sl, mine_raw, lane); break;
+            case 7: row_pass_kept<Layout, 32, 2>(weight_at, rec, sl, mine_raw, lane); break;
+            case 8: row_pass_kept<Layout, 32, 3>(weight_at, rec, sl, mine_raw, lane); break;
+            case 9: row_pass_kept<Layout, 64, 2>(weight_at, rec, sl, mine_raw, lane); break;
+            case 10: row_pass_kept<Layout, 64, 3>(weight_at, rec, sl, mine_raw, lane); break;
             default: row_pass_long<Layout>(weight_at, a.slots, rec, lane); break;
             }
         };
@@ -902,11 +915,11 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             const float w_o = __int_as_float(head.w);
             int z_new = head.x;
             if (head.y == kDrawInUnit)
-                z_new = topic_in_unit<Layout>(weight_at, a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
+                z_new = topic_in_unit<Layout, kNear>(weight_at, a.slots, (uint32_t)head.x, head.z << 2, w_o, rec->u);
             if (head.y == kDrawDense)
                 z_new = dense_bucket_search<kGroup>(pstar, cp, K, ng, ka->alpha, rec->u, head.z, w_o,
                                                     (double)w_o - (double)pstar[head.z]);
-            ka->z_next[tl.begin + b * batch + lane] = (uint16_t)z_new;
+            store_at<uint16_t>(ka->z_next + tl.begin, (uint32_t)(b * batch + lane) << 1, (uint16_t)z_new);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
