@@ -85,6 +85,9 @@ int mlda_workspace_bytes(int64_t D, int64_t T, int32_t V, int32_t K, size_t* byt
  * K: 1 .. 65,535 (MLDA_EINVAL outside).  A K whose column of p* does not fit the 160 KB of LDS
  * of a workgroup (beyond about 30,900) is sampled with p* in device memory: same results, several
  * times slower per token; the workspace then holds 512 such columns more.
+ * Environment, read here: MLDA_WIDE_SLOT_OFFSETS=1 makes the sampler address theta rows with 64-bit
+ * offsets, the form it otherwise takes only when the rows of a chunk fill more than 4 GiB (for
+ * tests; same results, a few per cent slower).
  */
 int mlda_create(mlda_ctx** out, const int64_t* doc_ptr, const int32_t* word_ids,
                 int64_t D, int32_t V, int32_t K, double alpha, double beta, uint64_t seed,

@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -475,6 +476,7 @@ struct mlda_ctx {
     hipStream_t stream = nullptr;
     int n_cus = 0, lds_limit = 0;
     bool far_weights = false;           // p* of the sampler's tiles in device memory (large K)
+    bool wide_slot_offsets = false;     // MLDA_WIDE_SLOT_OFFSETS: 64-bit unit addresses whatever the buffer's size
     float* far_pstar = nullptr;
     size_t sample_lds = 0;
     mlda::PhiView phi[2];                // [model_cur] is the current phi; two copies when streamed
@@ -834,7 +836,8 @@ int launch_sampler(mlda_ctx* c, const uint16_t* z_cur, uint16_t* z_next) {
     const int32_t grid = c->far_weights ? std::min<int32_t>(a.n_tiles, kFarStrips)
                                         : a.n_single + (a.n_tiles - a.n_single + a.run_tiles - 1) / a.run_tiles;
     void* kernel_args[] = {&a};
-    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs, slots_near(c->slots_bytes)), dim3((unsigned)grid),
+    HIP_TRY(hipLaunchKernel(sample_kernel_for(c->K, c->short_docs, slots_near(c->slots_bytes) && !c->wide_slot_offsets),
+                            dim3((unsigned)grid),
                             dim3((unsigned)(waves * mlda::kWave)), kernel_args, c->sample_lds, c->stream));
     return launch_check("sample_kernel");
 }
@@ -1040,6 +1043,9 @@ int device_limits(mlda_ctx* c) {
     HIP_TRY(hipDeviceGetAttribute(&c->lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
     c->Kpad = kpad_for(c->K);
     c->far_weights = far_weights_for(c->K);
+    // (a switch for tests: the 64-bit form is otherwise only reached by theta slots beyond 4 GiB)
+    const char* wide = std::getenv("MLDA_WIDE_SLOT_OFFSETS");
+    c->wide_slot_offsets = wide && wide[0] != '\0' && wide[0] != '0';
     c->sample_lds = c->far_weights ? mlda::sample_far_lds_bytes(c->Kpad, sample_waves_for(c->K))
                                    : mlda::sample_lds_bytes(c->Kpad, sample_waves_for(c->K));
     if (c->sample_lds > (size_t)c->lds_limit)

@@ -151,6 +151,25 @@ def test_edge_shapes(mlda, case):
     model.close()
 
 
+@pytest.mark.parametrize("case", [("tiny_rows", 60, 90, 65, 300), ("packed_rows", 30, 300, 1024, 400),
+                                  ("packed_rows_long_docs", 3, 300, 1100, 17500),
+                                  ("large_k", 300, 2000, 10000, 120), ("k_beyond_lds", 40, 300, 31000, 400)],
+                         ids=lambda c: c[0])
+def test_wide_slot_offsets(mlda, case, monkeypatch):
+    """The sampler kernels that address theta rows with 64-bit offsets (what rows beyond 4 GiB
+    need; the full-size test of 2.1e9 tokens reaches only one of them), on small inputs."""
+    name, D, V, K, mean_len = case
+    monkeypatch.setenv("MLDA_WIDE_SLOT_OFFSETS", "1")
+    c = corpus_synth.tiny(D=D, V=V, K=K, mean_len=mean_len, seed=len(name), name=name)
+    alpha, beta = 50.0 / K, 0.01
+    model = mlda.Mlda(c.doc_ptr, c.word_ids, V, K, alpha, beta, SEED)
+    model.init_random()
+    z = oracle.init_topics(c.T, K, SEED)
+    for it in (1, 2):
+        z = check_step(model, c, z, V, K, alpha, beta, SEED, it)
+    model.close()
+
+
 def test_long_document_with_more_topics_than_32bit_counters_fit(mlda):
     """A document of 2^16 tokens or more needs 32-bit counters in the theta rebuild; beyond
     32,768 topics they do not fit the LDS at once and the document is counted in two ranges of
