@@ -98,7 +98,7 @@ constexpr int kMinBatch = 8;    // tokens a wave takes at a time at least
 // phase: `nnz` says what kind (below), `off` and `u` hold it.
 struct __align__(16) TokenRec { // per-lane phase -> per-group phase, 32 bytes
     uint32_t off;               // slot offset of the token's theta row, 16-byte units
-    int32_t nnz;                // entries of the row
+    int32_t nnz;                // 16-byte units of entries of the row
     int32_t o;                  // current topic
     float w_o;                  // p*(o) with the token itself removed
     double u;
@@ -573,8 +573,7 @@ __device__ __forceinline__ void row_pass_long(const Weights& weight_at, const un
                                               int lane) {
     constexpr int UE = Layout::kUnitEntries;
     const RowCtx r = row_ctx(rec);
-    const int nnz = rec->nnz;
-    const int n_units = (nnz + UE - 1) / UE, n = (n_units + kWave - 1) / kWave;
+    const int n_units = rec->nnz, n = (n_units + kWave - 1) / kWave;
     const int u0 = lane * n;
     // the entry before the lane's first one (lanes past the row's end have no entries at all)
     const bool own_before = u0 < n_units &&
@@ -782,8 +781,9 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             const uint64_t id = (uint64_t)load_at<uint32_t>(ka->tok_id + tl.begin, (uint32_t)idx << 2);
             // the row's length sits in front of its entries: this read also brings the row's
             // first line on its way
-            mine.nnz = kNear ? load_at<int32_t>(a.slots, mine.off << 4)
-                             : *reinterpret_cast<const int32_t*>(a.slots + (size_t)mine.off * 16u);
+            const uint32_t entries = kNear ? load_at<uint32_t>(a.slots, mine.off << 4)
+                                           : *reinterpret_cast<const uint32_t*>(a.slots + (size_t)mine.off * 16u);
+            mine.nnz = (int)((entries + (uint32_t)(Layout::kUnitEntries - 1)) / (uint32_t)Layout::kUnitEntries);
             // (the seed too: the ten rounds' keys are then made where they are used, by the scalar
             // unit, and not once per kernel)
             mine.u = token_uniform(ka->seed, ka->iter, id);
@@ -815,13 +815,12 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // batch's end hold nnz = 0): the shape of every pass follows from these masks.
         const int n_here = min(batch, tl.count - b * batch);
         static_assert(kKeptUnits == 3, "the pass shapes assume three kept units per lane");
-        constexpr int UE = Layout::kUnitEntries;
-        const uint64_t over_4_1 = __ballot(mine.nnz > 4 * UE), over_4_2 = __ballot(mine.nnz > 8 * UE);
-        const uint64_t over_4_3 = __ballot(mine.nnz > 12 * UE), over_8_2 = __ballot(mine.nnz > 16 * UE);
-        const uint64_t over_8_3 = __ballot(mine.nnz > 24 * UE), over_16_2 = __ballot(mine.nnz > 32 * UE);
-        const uint64_t over_16_3 = __ballot(mine.nnz > 48 * UE), over_32_2 = __ballot(mine.nnz > 64 * UE);
-        const uint64_t over_32_3 = __ballot(mine.nnz > 96 * UE), over_64_2 = __ballot(mine.nnz > 128 * UE);
-        const uint64_t over_64_3 = __ballot(mine.nnz > 192 * UE);
+        const uint64_t over_4_1 = __ballot(mine.nnz > 4), over_4_2 = __ballot(mine.nnz > 8);
+        const uint64_t over_4_3 = __ballot(mine.nnz > 12), over_8_2 = __ballot(mine.nnz > 16);
+        const uint64_t over_8_3 = __ballot(mine.nnz > 24), over_16_2 = __ballot(mine.nnz > 32);
+        const uint64_t over_16_3 = __ballot(mine.nnz > 48), over_32_2 = __ballot(mine.nnz > 64);
+        const uint64_t over_32_3 = __ballot(mine.nnz > 96), over_64_2 = __ballot(mine.nnz > 128);
+        const uint64_t over_64_3 = __ballot(mine.nnz > 192);
         auto any = [](uint64_t mask, int t0, uint32_t window) {      // 1 if a token of the window is set
             const uint32_t w = (uint32_t)(mask >> t0) & window;
             return min(1, (int)__builtin_popcount(w));      // stays scalar arithmetic
@@ -853,7 +852,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             rec = my_rec + min(t0 + geo_rel, kWave - 1);
             const uint2 where = *reinterpret_cast<const uint2*>(rec);
             // units the lane loads: those of the shape that the row still has from its first on
-            const int n_mine = live ? min((int)((where.y + (uint32_t)(UE - 1)) / (uint32_t)UE) - geo_q0, nu) : 0;
+            const int n_mine = live ? min((int)where.y - geo_q0, nu) : 0;
             if constexpr (kNear) {
                 const uint32_t row_bytes = (where.x + 1u + (uint32_t)geo_q0) << 4;
 #pragma unroll
