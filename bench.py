@@ -28,13 +28,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # this chip, WRITE_SIZE by 1.000 (same summaries).
 FETCH_SCALE, WRITE_SCALE = 2.000, 1.000
 MEASURED_TRAFFIC_KIB = {
-    ("C4", "init"): (7.12111e7, 1.65612e6, "profiles/sample_kernel_C4.md"),
-    ("C3", "init"): (1.227e7, 2.24583e5, "profiles/sample_kernel_C3_C5.md"),
-    ("C5", "init"): (2.95307e7, 2.50377e6, "profiles/sample_kernel_C3_C5.md"),
+    ("C4", "init"): (7.18155e7, 1.66019e6, "profiles/sample_kernel_C4.md"),
+    ("C3", "init"): (1.22944e7, 2.24598e5, "profiles/sample_kernel_C3_C5.md"),
+    ("C5", "init"): (2.89505e7, 1.38495e6, "profiles/sample_kernel_C3_C5.md"),
 }
 # VALU wave-instructions per sampling launch (SQ_INSTS_VALU, same summaries): the sampler's other
 # limit is instruction issue, 1024 SIMDs x 2.4 GHz / 4 cycles per wave-instruction
-MEASURED_VALU_INSTS = {("C4", "init"): 1.68094e10, ("C3", "init"): 4.2501e9, ("C5", "init"): 6.56475e9}
+MEASURED_VALU_INSTS = {("C4", "init"): 1.65364e10, ("C3", "init"): 4.18612e9, ("C5", "init"): 6.47468e9}
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4.0
 
 
