@@ -282,7 +282,7 @@ struct TinyRows {
 };
 
 // Unit `unit` of the row in slot `off`.  Every lane loads: a lane without entries reads the
-// padding entries that the library keeps in the first 16 bytes of the slot buffer (no slot
+// padding entries that the library keeps in the first 64 bytes of the slot buffer (no slot
 // starts there).
 __device__ __forceinline__ uint4 load_unit(const unsigned char* slots, uint32_t off, int unit, bool on) {
     static_assert(kRowHeader == 16, "a row's entries start one 16-byte unit into its slot");
@@ -771,6 +771,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
         // block again in every batch (scalar loads) instead of being kept in scalar registers
         // through the passes: there are not enough of those, and what does not fit is parked in
         // lanes of a vector register, every read of which takes a vector issue slot.
+        // (SampleArgs is the kernel's only parameter, so the argument block starts with it.)
         typedef __attribute__((address_space(4))) const SampleArgs* ArgsPtr;
         ArgsPtr ka = (ArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
         asm volatile("" : "+s"(ka));
@@ -873,7 +874,7 @@ __global__ __launch_bounds__(kWaves * kWave) void sample_kernel(const SampleArgs
             TokenRec* rec = rec_next;
             t_next += kWave >> lanes_log2(shape);
             // The request is made whether or not a pass follows (after the batch's last pass
-            // every lane loads the padding unit): the number of loads in flight behind this
+            // every lane loads padding units): the number of loads in flight behind this
             // pass's own is then the same on every path, and the pass waits for its own rows
             // only, not for the first of the following pass's as well.
             const int t_req = min(t_next, kWave - 1);
